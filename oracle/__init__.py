@@ -1,0 +1,233 @@
+"""TEST INFRASTRUCTURE: ctypes front end of the CPU oracle (oracle/prs_oracle.c).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package.  It never imports the GPU package, and the GPU package never imports
+it.  `build()` compiles the C file with gcc; loading builds on demand.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = [os.path.join(_HERE, "prs_oracle.c"), os.path.join(_HERE, "greedy_body.inc")]
+_LIB_PATH = os.path.join(_HERE, "_build", "libprs_oracle.so")
+_lib = None
+
+UNI, BI = 0, 1
+MODE_LITERAL, MODE_EVENT, MODE_PRUNE = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle.  No FMA contraction, no fast-math: every product and
+    sum is rounded on its own, as the cost model is stated."""
+    os.makedirs(os.path.dirname(_LIB_PATH), exist_ok=True)
+    stale = force or not os.path.exists(_LIB_PATH) or any(
+        os.path.getmtime(s) > os.path.getmtime(_LIB_PATH) for s in _SRC)
+    if stale:
+        tmp = _LIB_PATH + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fwrapv",
+                               "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC[0]])
+        os.replace(tmp, _LIB_PATH)
+    return _LIB_PATH
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_exhaustive_uni_i64.restype = C.c_int64
+        _lib.orc_ceil_log2.restype = C.c_int32
+        for suf in ("_i64", "_f64"):
+            getattr(_lib, "orc_binomial_construct" + suf).restype = C.c_int64 if suf == "_i64" else C.c_double
+            getattr(_lib, "orc_pipeline_construct" + suf).restype = C.c_int64 if suf == "_i64" else C.c_double
+            getattr(_lib, "orc_butterfly_steps" + suf).restype = C.c_double
+    return _lib
+
+
+def _ptr(a, ctype):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _ct(cost):
+    if cost == "i64":
+        return np.int64, C.c_int64, "_i64"
+    if cost == "f64":
+        return np.float64, C.c_double, "_f64"
+    raise ValueError(cost)
+
+
+def ceil_log2(v: int) -> int:
+    return int(lib().orc_ceil_log2(C.c_int64(v)))
+
+
+def segmentation(m: int, q_req: int):
+    """(q_eff, sz_full, sz_last) of the equi-segmentation of m."""
+    q, s, l = C.c_int64(), C.c_int64(), C.c_int64()
+    lib().orc_segmentation(C.c_int64(int(m)), C.c_int64(int(q_req)), C.byref(q), C.byref(s), C.byref(l))
+    return q.value, s.value, l.value
+
+
+def equi_sizes(m: int, q_req: int) -> np.ndarray:
+    q, s, l = segmentation(m, q_req)
+    sizes = np.full(q, s, dtype=np.int64)
+    sizes[-1] = l
+    return sizes
+
+
+@dataclass
+class Schedule:
+    src: np.ndarray
+    dst: np.ndarray
+    seg: np.ndarray
+    t: np.ndarray
+    T: object
+    status: int = 0
+    x_final: np.ndarray | None = None
+    root_done: np.ndarray | None = None
+    n_visits: int = 0
+
+
+def uni_greedy(p, sizes, alpha, beta, gamma, cost="i64", want_schedule=True) -> Schedule:
+    npt, ct, suf = _ct(cost)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    q = int(sizes.shape[0])
+    n = (p - 1) * q if want_schedule else 0
+    src = np.empty(n, np.int32) if want_schedule else None
+    dst = np.empty(n, np.int32) if want_schedule else None
+    seg = np.empty(n, np.int32) if want_schedule else None
+    t = np.empty(n, npt) if want_schedule else None
+    xf = np.empty(p, npt)
+    T = ct()
+    rc = getattr(lib(), "orc_uni_greedy" + suf)(
+        C.c_int32(p), C.c_int32(q), _ptr(sizes, C.c_int64), ct(alpha), ct(beta), ct(gamma),
+        _ptr(src, C.c_int32), _ptr(dst, C.c_int32), _ptr(seg, C.c_int32), _ptr(t, ct), _ptr(xf, ct), C.byref(T))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return Schedule(src, dst, seg, t, T.value, 0, xf)
+
+
+def bi_greedy(p, sizes, alpha, beta, gamma, cost="i64", mode=MODE_EVENT, want_schedule=True) -> Schedule:
+    npt, ct, suf = _ct(cost)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    q = int(sizes.shape[0])
+    n = (p - 1) * q if want_schedule else 0
+    src = np.empty(n, np.int32) if want_schedule else None
+    dst = np.empty(n, np.int32) if want_schedule else None
+    seg = np.empty(n, np.int32) if want_schedule else None
+    t = np.empty(n, npt) if want_schedule else None
+    rd = np.zeros(q, npt)
+    T = ct()
+    npairs, nvis = C.c_int64(), C.c_int64()
+    rc = getattr(lib(), "orc_bi_greedy" + suf)(
+        C.c_int32(p), C.c_int32(q), _ptr(sizes, C.c_int64), ct(alpha), ct(beta), ct(gamma), C.c_int(mode),
+        C.c_int64(n), _ptr(src, C.c_int32), _ptr(dst, C.c_int32), _ptr(seg, C.c_int32), _ptr(t, ct),
+        _ptr(rd, ct), C.byref(npairs), C.byref(nvis), C.byref(T))
+    if rc < 0:
+        raise MemoryError("oracle allocation failed")
+    if want_schedule and rc == 0:
+        assert npairs.value == n, (npairs.value, n)
+    return Schedule(src, dst, seg, t, T.value, rc, None, rd, nvis.value)
+
+
+def closed_forms(model, p, q, m, sz, alpha, beta, gamma, cost="i64"):
+    """dict of the closed-form times: binomial, pipeline, binary, revopt (cost
+    type), butterfly and lower_bound (always float)."""
+    npt, ct, suf = _ct(cost)
+    out = np.empty(4, npt)
+    getattr(lib(), "orc_closed_forms" + suf)(C.c_int(model), C.c_int32(p), C.c_int32(q), C.c_int64(int(m)),
+                                             C.c_int64(int(sz)), ct(alpha), ct(beta), ct(gamma), _ptr(out, ct))
+    o2 = np.empty(2, np.float64)
+    lib().orc_butterfly_and_bound(C.c_int(model), C.c_int32(p), C.c_int64(int(m)), C.c_double(float(alpha)),
+                                  C.c_double(float(beta)), C.c_double(float(gamma)), _ptr(o2, C.c_double))
+    return {"binomial": out[0].item(), "pipeline": out[1].item(), "binary": out[2].item(),
+            "revopt": out[3].item(), "butterfly": float(o2[0]), "lower_bound": float(o2[1])}
+
+
+def binomial_construct(p, m, alpha, beta, gamma, cost="i64"):
+    _, ct, suf = _ct(cost)
+    return getattr(lib(), "orc_binomial_construct" + suf)(C.c_int32(p), C.c_int64(int(m)), ct(alpha), ct(beta), ct(gamma))
+
+
+def pipeline_construct(p, sizes, alpha, beta, gamma, cost="i64"):
+    _, ct, suf = _ct(cost)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    return getattr(lib(), "orc_pipeline_construct" + suf)(C.c_int32(p), C.c_int32(sizes.shape[0]), _ptr(sizes, C.c_int64),
+                                                          ct(alpha), ct(beta), ct(gamma))
+
+
+def butterfly_steps(p, m, alpha, beta, gamma, cost="f64"):
+    _, ct, suf = _ct(cost)
+    return getattr(lib(), "orc_butterfly_steps" + suf)(C.c_int32(p), C.c_int64(int(m)), ct(alpha), ct(beta), ct(gamma))
+
+
+def exhaustive_uni(p, sizes, alpha, beta, gamma) -> int:
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    return int(lib().orc_exhaustive_uni_i64(C.c_int32(p), C.c_int32(sizes.shape[0]), _ptr(sizes, C.c_int64),
+                                            C.c_int64(alpha), C.c_int64(beta), C.c_int64(gamma)))
+
+
+def replay(p, seg_elem_offset, src, dst, seg, buf: np.ndarray) -> np.ndarray:
+    """Replays the schedule on a copy of buf (p rows); returns row 0."""
+    work = np.ascontiguousarray(buf).copy()
+    assert work.shape[0] == p
+    off = np.ascontiguousarray(seg_elem_offset, dtype=np.int64)
+    src = np.ascontiguousarray(src, np.int32); dst = np.ascontiguousarray(dst, np.int32)
+    seg = np.ascontiguousarray(seg, np.int32)
+    if work.dtype == np.int32:
+        fn, ct = lib().orc_replay_i32, C.c_int32
+    elif work.dtype == np.float32:
+        fn, ct = lib().orc_replay_f32, C.c_float
+    else:
+        raise TypeError(work.dtype)
+    fn(C.c_int32(p), C.c_int64(work.shape[1]), _ptr(off, C.c_int64), C.c_int64(src.shape[0]),
+       _ptr(src, C.c_int32), _ptr(dst, C.c_int32), _ptr(seg, C.c_int32), _ptr(work, ct))
+    return work[0].copy()
+
+
+# ---------------------------------------------------------------------------
+# Batch front end: one configuration after another, results in the layout the
+# C-ABI library uses, so tests can compare array against array.
+# ---------------------------------------------------------------------------
+@dataclass
+class BatchResult:
+    T_greedy: np.ndarray
+    T_binomial: np.ndarray
+    T_pipeline: np.ndarray
+    T_binary: np.ndarray
+    T_revopt: np.ndarray
+    T_butterfly: np.ndarray
+    T_lower_bound: np.ndarray
+    q_eff: np.ndarray
+    status: np.ndarray
+
+
+def simulate_batch(cfgs, model, mode=MODE_EVENT | MODE_PRUNE, index=None) -> BatchResult:
+    """Completion times and baselines for every configuration (or those in
+    `index`), computed one by one."""
+    npt, _, _ = _ct(cfgs.cost)
+    idx = np.arange(len(cfgs)) if index is None else np.asarray(index)
+    n = idx.shape[0]
+    res = BatchResult(*(np.zeros(n, npt) for _ in range(5)), np.zeros(n), np.zeros(n),
+                      np.zeros(n, np.int32), np.zeros(n, np.int32))
+    for o, i in enumerate(idx):
+        p, m, qr = int(cfgs.p[i]), int(cfgs.m[i]), int(cfgs.q_req[i])
+        a, b, g = cfgs.alpha[i].item(), cfgs.beta[i].item(), cfgs.gamma[i].item()
+        q, sz, _ = segmentation(m, qr)
+        sizes = equi_sizes(m, qr)
+        if model == UNI:
+            s = uni_greedy(p, sizes, a, b, g, cfgs.cost, want_schedule=False)
+        else:
+            s = bi_greedy(p, sizes, a, b, g, cfgs.cost, mode=mode, want_schedule=False)
+        cf = closed_forms(model, p, q, m, sz, a, b, g, cfgs.cost)
+        res.T_greedy[o] = s.T
+        res.T_binomial[o] = cf["binomial"]; res.T_pipeline[o] = cf["pipeline"]
+        res.T_binary[o] = cf["binary"]; res.T_revopt[o] = cf["revopt"]
+        res.T_butterfly[o] = cf["butterfly"]; res.T_lower_bound[o] = cf["lower_bound"]
+        res.q_eff[o] = q
+        res.status[o] = s.status
+    return res
