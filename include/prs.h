@@ -1,0 +1,166 @@
+/*
+ * prs.h -- C ABI of the pipelined-reduction-schedule library for AMD gfx950.
+ *
+ * The library constructs and times reduction schedules on a machine of p
+ * homogeneous, fully connected processors under the linear cost model of
+ * Lowery & Langou, "A Greedy Algorithm for Optimally Pipelining a Reduction"
+ * (Section 2): sending a segment of sz elements keeps the sender busy
+ * tcomm = alpha + beta*sz and the receiver tcomm + tcomp, tcomp = gamma*sz;
+ * communication and computation never overlap on a processor.  A message of
+ * m elements is cut into q segments of equal size, the last possibly smaller.
+ * A reduction is a set of (p-1)q send/receive pairs (Section 5, first
+ * paragraph); its completion time is the time the root, processor 0,
+ * finishes its last combine.
+ *
+ * Conventions, valid for every entry point:
+ *  - "device" pointers address GPU memory of the current HIP device, "host"
+ *    pointers ordinary memory.  All buffers are allocated and owned by the
+ *    caller; the library allocates no device memory and keeps no state
+ *    between calls.  Inputs are never written.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued on it and the call returns without synchronising.
+ *  - `workspace` is device scratch of at least prs_workspace_bytes(...)
+ *    bytes, 256-byte aligned, private to the call until the stream has
+ *    drained it.
+ *  - The return value is a prs_status for the call as a whole; when it is
+ *    not PRS_OK nothing has been enqueued.  Problems of a single
+ *    configuration are reported in its cfg_status entry (prs_cfg_status):
+ *    its results are then -1 (integers) or NaN (doubles), its schedule range
+ *    is left untouched, and the rest of the batch is unaffected.
+ *  - Costs are either all int64_t (integer time units) or all double
+ *    (seconds), selected by prs_cost.  Doubles are combined as
+ *    tcomm = alpha + (beta*sz), end of send = t + tcomm, end of combine =
+ *    (t + tcomm) + tcomp, every operation rounded on its own (no FMA).
+ *    Integer overflow is not detected.
+ */
+#ifndef PRS_H
+#define PRS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PRS_OK = 0, PRS_EINVAL = 1, PRS_ENOSPC = 2, PRS_EDEVICE = 3 } prs_status;
+typedef enum { PRS_UNI = 0, PRS_BI = 1 } prs_model;      /* one port / separate send and receive ports (Section 2) */
+typedef enum { PRS_COST_I64 = 0, PRS_COST_F64 = 1 } prs_cost;
+typedef enum { PRS_I32 = 0, PRS_F32 = 1 } prs_dtype;
+typedef enum {
+    PRS_CFG_OK = 0,
+    PRS_CFG_BAD_PARAM = 1,   /* p < 2, q_req < 1, m < 1, a negative or non-finite cost, or tcomm = 0 */
+    PRS_CFG_TOO_LARGE = 2,   /* p > p_max, q_req > q_max, or the schedule does not fit pair_capacity */
+    PRS_CFG_STALLED = 3      /* time could not advance (a cost vanished against the clock in rounding) */
+} prs_cfg_status;
+typedef enum { PRS_CALL_SIMULATE = 0, PRS_CALL_SCHEDULE = 1, PRS_CALL_REPLAY = 2, PRS_CALL_OFFSETS = 3 } prs_call;
+
+/* A batch of n configurations, structure of arrays, DEVICE pointers.
+ * q_req is the requested number of segments: the segment size is
+ * ceil(m / q_req) and q_eff = ceil(m / size) <= q_req segments are used
+ * (Section 2, last paragraph).  alpha, beta, gamma point to int64_t or double
+ * according to the prs_cost argument of the call. */
+typedef struct prs_configs {
+    const int32_t *p;
+    const int32_t *q_req;
+    const int64_t *m;
+    const void *alpha;
+    const void *beta;
+    const void *gamma;
+} prs_configs;
+
+/* Result columns of simulate_completion_batch, DEVICE pointers to n entries
+ * each; any of them may be NULL to skip that column.  greedy..revopt have the
+ * cost type of the call, butterfly and lower_bound are always double. */
+typedef struct prs_times {
+    void *greedy;        /* uni-greedy (Algorithm 1) or bi-greedy (Algorithm 2) completion time */
+    void *binomial;      /* ceil(log2 p)(alpha + beta m + gamma m)                 Tables I, III */
+    void *pipeline;      /* uni (p-1+2(q-1)) r, bi (p+q-2) r, r = alpha+beta sz+gamma sz          */
+    void *binary;        /* uni (2(N-1)+4(q-1)) r, bi 2(N+q-2) r, N = ceil(log2(p+1))             */
+    void *revopt;        /* reversed optimal broadcast (ceil(log2 p)+q-1) r         Table III    */
+    double *butterfly;   /* 2 L alpha + 2 (p-1)/p beta m + (p-1)/p gamma m          Table III    */
+    double *lower_bound; /* L alpha + B + (p-1)/p gamma m; B = 2 m beta (uni, p > 2), m beta otherwise
+                            (Table II, first row; reference line of Figure 6) */
+    int32_t *q_eff;      /* number of segments actually used */
+    int32_t *cfg_status; /* prs_cfg_status */
+} prs_times;
+
+/* Bytes of device scratch the given call needs for a batch of n
+ * configurations with p <= p_max and q_req <= q_max (for PRS_CALL_REPLAY:
+ * n = 1, p_max = p, q_max = q).  Host function, no GPU work. */
+size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_max, int32_t q_max);
+
+/*
+ * Completion time of the greedy schedule of every configuration, next to the
+ * closed-form times of the standard algorithms it is compared with (Sections
+ * 4, 5.2, 6.1).  model = PRS_UNI runs Algorithm 1 (Section 5): per segment,
+ * p-1 times, the two processors with the smallest ready times pair up at the
+ * larger of the two.  model = PRS_BI runs Algorithm 2 (Section 6.2), its unit
+ * time step replaced by a jump to the next time a port frees.
+ * cfg, out: host structs holding device pointers.  p_max, q_max: upper bounds
+ * on p and q_req in the batch (they size the workspace).
+ * Errors: PRS_EINVAL for a NULL struct/array, n < 0, bad enum or bounds;
+ * PRS_ENOSPC if workspace_bytes is too small; PRS_EDEVICE if a launch fails.
+ */
+int simulate_completion_batch(const prs_configs *cfg, int64_t n, int model, int cost,
+                              int32_t p_max, int32_t q_max, const prs_times *out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * pair_offset[i] = sum over j < i of (p_j - 1) * q_eff_j, for i = 0..n
+ * (invalid configurations count 0): where configuration i's pairs start in
+ * the arrays of greedy_schedule_batch.  pair_offset: device, n+1 entries.
+ */
+int prs_pair_offsets(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t q_max,
+                     int64_t *pair_offset, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The greedy schedule itself (Section 5, Algorithm 1; Section 6.2, Algorithm
+ * 2): for configuration i, pairs pair_offset[i] .. pair_offset[i+1]-1 of the
+ * device arrays src, dst, seg (int32) and t_start (cost type) receive, in the
+ * order the algorithm emits them, the sending processor, the receiving
+ * processor, the 0-based segment and the start time of each send/receive
+ * pair.  Ties between equal ready times (Algorithm 1) go to the smaller
+ * processor index and the first of the two sends unless it is the root.
+ * Algorithm 2 emits by time, then segment, then position in its paired lists.
+ * Any of src/dst/seg/t_start/T_greedy may be NULL.  A configuration whose
+ * range would pass pair_capacity gets PRS_CFG_TOO_LARGE and writes nothing.
+ */
+int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost,
+                          int32_t p_max, int32_t q_max,
+                          const int64_t *pair_offset, int64_t pair_capacity,
+                          int32_t *src, int32_t *dst, int32_t *seg, void *t_start,
+                          void *T_greedy, int32_t *cfg_status,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Executes one schedule on data (Section 4: "after a receiving processor
+ * receives a segment it will combine its segment with the segment
+ * received"): with buf_i = in + i*stride_elems (i < p, n_elems values each),
+ * applying buf_dst[segment] = buf_dst[segment] + buf_src[segment] pair by
+ * pair in the order given leaves the reduction in buf_0; that result, with
+ * exactly that association of the additions, is written to out (n_elems
+ * values).  `in` is not modified.  Segment k covers elements
+ * seg_elem_offset[k] .. seg_elem_offset[k+1]-1 (HOST array, q+1 entries,
+ * non-decreasing from 0 to n_elems; read before the call returns).
+ * src, dst, seg: device, n_pairs = (p-1)q entries, in which every non-root
+ * processor sends every segment exactly once, after all it receives of it.
+ * dtype: PRS_I32 (wrapping add) or PRS_F32 (IEEE add, no FMA, denormals
+ * kept).  status: device int32, receives 0, or 1 if the schedule is not a
+ * set of q in-trees on p processors, or 2 if a combine tree needs more
+ * nested partial sums than the kernel holds (then out is not written).
+ * Limits: 2 <= p <= 4096, q <= 65536, (p-1)q < 2^31.
+ */
+int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset,
+                     const int32_t *src, const int32_t *dst, const int32_t *seg, int64_t n_pairs,
+                     const void *in, int64_t stride_elems, int64_t n_elems, int dtype,
+                     void *out, int32_t *status,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Version of the ABI, bumped on any incompatible change. */
+int prs_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRS_H */

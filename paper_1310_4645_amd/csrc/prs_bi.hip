@@ -1,0 +1,275 @@
+// Bi-greedy schedules (Lowery & Langou, Algorithm 2, Section 6.2) on gfx950.
+//
+// One 64-lane wavefront runs one configuration.  Algorithm 2 walks over time;
+// at each time t it visits the segments from the first unfinished one upwards
+// and, per segment j, builds three index lists over the processors that still
+// hold j and are not excluded by a computation: send port free only, receive
+// port free only, both free.  The processors with both ports free are dealt
+// to the shorter list (first entries receive, last entries send), the first
+// l = min(#send, #recv) entries are paired entry by entry, and the ports and
+// the pending computation of the paired processors are updated.
+//
+// Here every list is a bit set over the processors (64 per machine word), so
+// one lane classifies 64 processors with a few logic operations, list lengths
+// are population counts, "first k entries" is a rank select inside a word and
+// list positions come from wavefront prefix sums.  The unit time step is
+// replaced by a jump to the next time a send or receive port frees: no new
+// pair can form in between.  Segments in which every processor has sent, and
+// visits after the last free send or receive port is used up, are skipped:
+// they cannot produce a pair.
+//
+// A processor's computation interval [C1, C2) always ends when its receive
+// port frees, so C2 is not stored separately.
+#include "prs_device.h"
+#include "prs_launch.h"
+
+namespace prs {
+
+__host__ __device__ inline size_t bi_align(size_t v) { return (v + 255) / 256 * 256; }
+
+struct BiLayout {
+    size_t S, R, C1, nsent, masks, pref, sendList, recvList, rem, sent, total;
+    int W;
+};
+
+__host__ __device__ inline BiLayout bi_layout(int32_t p_max, int32_t q_max)
+{
+    BiLayout L;
+    const size_t p = static_cast<size_t>(p_max), q = static_cast<size_t>(q_max);
+    L.W = static_cast<int>((p + 63) / 64);
+    size_t o = 0;
+    L.S = o; o += bi_align(p * 8);
+    L.R = o; o += bi_align(p * 8);
+    L.C1 = o; o += bi_align(p * 8);
+    L.nsent = o; o += bi_align(p * 4);
+    L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 9);   // 9 word arrays
+    L.pref = o; o += bi_align(static_cast<size_t>(L.W) * 4 * 2);
+    L.sendList = o; o += bi_align((p / 2 + 1) * 4);
+    L.recvList = o; o += bi_align((p / 2 + 1) * 4);
+    L.rem = o; o += bi_align(q * 4);
+    L.sent = o; o += bi_align(static_cast<size_t>(L.W) * q * 8);
+    L.total = o;
+    return L;
+}
+
+size_t bi_slot_bytes(int32_t p_max, int32_t q_max) { return bi_layout(p_max, q_max).total; }
+
+template <typename T, bool kSched>
+__device__ T run_bi(const Config<T> &c, char *slot, const BiLayout &lay, const SchedOut &sched, int64_t out_base,
+                    int32_t *status)
+{
+    const int lane = lane_id();
+    const int p = c.p, q = c.q;
+    const int W = (p + 63) >> 6;                        // words in use (<= lay.W)
+    T *S = reinterpret_cast<T *>(slot + lay.S);
+    T *R = reinterpret_cast<T *>(slot + lay.R);
+    T *C1 = reinterpret_cast<T *>(slot + lay.C1);
+    int32_t *nsent = reinterpret_cast<int32_t *>(slot + lay.nsent);
+    uint64_t *mk = reinterpret_cast<uint64_t *>(slot + lay.masks);
+    uint64_t *sfree = mk, *rfree = mk + lay.W, *compF = mk + 2 * lay.W, *compL = mk + 3 * lay.W;
+    uint64_t *soW = mk + 4 * lay.W, *roW = mk + 5 * lay.W, *frW = mk + 6 * lay.W;
+    uint64_t *sendSet = mk + 7 * lay.W, *recvSet = mk + 8 * lay.W;
+    int32_t *prefS = reinterpret_cast<int32_t *>(slot + lay.pref), *prefR = prefS + lay.W;
+    int32_t *sendList = reinterpret_cast<int32_t *>(slot + lay.sendList);
+    int32_t *recvList = reinterpret_cast<int32_t *>(slot + lay.recvList);
+    int32_t *rem = reinterpret_cast<int32_t *>(slot + lay.rem);
+    uint64_t *sent = reinterpret_cast<uint64_t *>(slot + lay.sent);      // [q][W]
+
+    for (int i = lane; i < p; i += kWave) { S[i] = 0; R[i] = 0; C1[i] = 0; nsent[i] = 0; }
+    for (int j = lane; j < q; j += kWave) rem[j] = p - 1;
+    for (int64_t k = lane; k < static_cast<int64_t>(q) * W; k += kWave) sent[k] = 0;
+    __syncthreads();
+
+    const T kInf = CostTraits<T>::inf();
+    T t = 0, Tmax = 0;
+    int ndone = 0, segStart = 0;
+    int64_t emitted = 0;
+    const int64_t max_events = 4 * static_cast<int64_t>(p) * q + 16;
+    for (int64_t ev = 0;; ++ev) {
+        if (ev > max_events) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
+        // ---- port and computation state of every processor at time t, as bit sets
+        T minOld = kInf;
+        int cs = 0, cr = 0;
+        for (int w = 0; w < W; ++w) {
+            const int i = w * kWave + lane;
+            const bool in = i < p;
+            const T s = in ? S[i] : 0, r = in ? R[i] : 0, c1 = in ? C1[i] : 0;
+            const int32_t nsnt = in ? nsent[i] : q;
+            const bool live = in && (i == 0 || nsnt < q);          // still a member of some segment
+            const bool sf = live && i != 0 && s <= t;              // the root never sends
+            const bool rf = live && r <= t;
+            const bool busy = in && c1 <= t && t < r;              // computing now
+            const bool pend = in && t < c1;                        // computation scheduled ahead
+            const bool cF = busy || (pend && t + c.c_full > c1);
+            const bool cL = busy || (pend && t + c.c_last > c1);
+            if (in && s > t && s < minOld) minOld = s;
+            if (in && r > t && r < minOld) minOld = r;
+            const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL);
+            if (lane == 0) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; }
+            cs += __popcll(bsf & ~bcL);
+            cr += __popcll(brf & ~bcL);
+        }
+        minOld = wave_min(minOld);
+        __syncthreads();
+        T minNew = kInf;
+        while (segStart < q && rem[segStart] == 0) ++segStart;
+        for (int j = segStart; j < q; ++j) {
+            if (cs == 0 || cr == 0) break;               // no further pair can form at this t
+            int remj = rem[j];
+            if (remj == 0) continue;                     // everybody has sent segment j
+            const bool last = j == q - 1;
+            const T cj = last ? c.c_last : c.c_full, gj = last ? c.g_last : c.g_full;
+            // ---- pass A: the three lists of this visit as bit sets, and their lengths
+            int ns_ = 0, nr_ = 0, nf_ = 0;
+            for (int w0 = 0; w0 < W; w0 += kWave) {
+                const int w = w0 + lane;
+                if (w < W) {
+                    uint64_t valid = ~UINT64_C(0);
+                    if (w == W - 1 && (p & 63)) valid = (UINT64_C(1) << (p & 63)) - 1;
+                    const uint64_t memb = ~sent[static_cast<size_t>(j) * W + w] & valid;
+                    const uint64_t comp = last ? compL[w] : compF[w];
+                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w];
+                    const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
+                    soW[w] = so; roW[w] = ro; frW[w] = fr;
+                    ns_ += __popcll(so); nr_ += __popcll(ro); nf_ += __popcll(fr);
+                }
+            }
+            ns_ = wave_sum(ns_); nr_ = wave_sum(nr_); nf_ = wave_sum(nf_);
+            // ---- processors with both ports free go to the shorter list
+            int toSendLast, toRecvFirst;
+            if (ns_ == nr_) {
+                toSendLast = toRecvFirst = nf_ / 2;
+            } else if (ns_ < nr_) {
+                const int y = nr_ - ns_, mm = nf_ < y ? nf_ : y, xx = (nf_ - mm) / 2;
+                toSendLast = mm + xx; toRecvFirst = xx;
+            } else {
+                const int y = ns_ - nr_, mm = nf_ < y ? nf_ : y, xx = (nf_ - mm) / 2;
+                toRecvFirst = mm + xx; toSendLast = xx;
+            }
+            const int sN = ns_ + toSendLast, rN = nr_ + toRecvFirst;
+            const int l = sN < rN ? sN : rN;
+            if (l == 0) continue;
+            // ---- pass B: final send and receive sets (first l of each), word by word with running ranks
+            int carryF = 0, carryS = 0, carryR = 0;
+            for (int w0 = 0; w0 < W; w0 += kWave) {
+                const int w = w0 + lane;
+                const bool on = w < W;
+                const uint64_t fr = on ? frW[w] : 0, so = on ? soW[w] : 0, ro = on ? roW[w] : 0;
+                const int pf = __popcll(fr);
+                const int incF = wave_inclusive_scan(pf);
+                const int exF = carryF + incF - pf;                       // free-list rank of this word's first entry
+                const uint64_t frR = lowest_bits(fr, toRecvFirst - exF);
+                const uint64_t frS = highest_bits(fr, exF + pf - (nf_ - toSendLast));
+                uint64_t sset = so | frS, rset = ro | frR;
+                const int ps = __popcll(sset), pr = __popcll(rset);
+                const int incS = wave_inclusive_scan(ps), incR = wave_inclusive_scan(pr);
+                const int exS = carryS + incS - ps, exR = carryR + incR - pr;
+                sset = lowest_bits(sset, l - exS);
+                rset = lowest_bits(rset, l - exR);
+                if (on) {
+                    sendSet[w] = sset; recvSet[w] = rset; prefS[w] = exS; prefR[w] = exR;
+                    sent[static_cast<size_t>(j) * W + w] |= sset;
+                    sfree[w] &= ~sset;
+                    rfree[w] &= ~rset;
+                }
+                carryF += __shfl(incF, kWave - 1, kWave);
+                carryS += __shfl(incS, kWave - 1, kWave);
+                carryR += __shfl(incR, kWave - 1, kWave);
+            }
+            __syncthreads();
+            // ---- pass C: bit sets -> index lists in ascending processor order
+            for (int w = 0; w < W; ++w) {
+                const uint64_t ss = sendSet[w], rs = recvSet[w];
+                if ((ss | rs) == 0) continue;
+                if ((ss >> lane) & 1) sendList[prefS[w] + rank_below(ss)] = w * kWave + lane;
+                if ((rs >> lane) & 1) recvList[prefR[w] + rank_below(rs)] = w * kWave + lane;
+            }
+            __syncthreads();
+            // ---- pass D: entry-wise pairing
+            const T tc = t + cj, tr = tc + gj;
+            if (!(tc > t)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
+            for (int e = lane; e < l; e += kWave) {
+                const int32_t a = sendList[e], b = recvList[e];
+                S[a] = tc;
+                nsent[a] += 1;
+                R[b] = tr;
+                C1[b] = tc;
+                if (kSched) {
+                    const int64_t o = out_base + emitted + e;
+                    if (sched.src) sched.src[o] = a;
+                    if (sched.dst) sched.dst[o] = b;
+                    if (sched.seg) sched.seg[o] = j;
+                    if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                }
+            }
+            emitted += l;
+            if (tc < minNew) minNew = tc;
+            if (tr < minNew) minNew = tr;
+            cs -= l; cr -= l;
+            remj -= l;
+            if (lane == 0) rem[j] = remj;
+            if (remj == 0) {                              // only the root is left: it finishes after the last arrival
+                if (tr > Tmax) Tmax = tr;
+                ++ndone;
+            }
+            __syncthreads();
+        }
+        if (ndone == q) break;
+        const T tn = minOld < minNew ? minOld : minNew;
+        if (!(tn < kInf)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
+        t = tn;
+    }
+    return Tmax;
+}
+
+template <typename T, bool kSched>
+__global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, int model,
+                                                   TimesOut times, SchedOut sched, char *slots, size_t slot_bytes,
+                                                   unsigned long long *ticket)
+{
+    __shared__ unsigned long long s_next;
+    const int lane = lane_id();
+    const BiLayout lay = bi_layout(p_max, q_max);
+    char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
+    for (;;) {
+        if (lane == 0) s_next = atomicAdd(ticket, 1ULL);
+        __syncthreads();
+        const int64_t i = static_cast<int64_t>(s_next);
+        __syncthreads();
+        if (i >= n) break;
+        Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
+        if (!kSched && lane == 0) write_closed_forms<T>(times, i, c, model);
+        int32_t status = c.status;
+        int64_t base = 0;
+        if (kSched && status == PRS_CFG_OK) {
+            base = sched.pair_offset[i];
+            const int64_t cnt = static_cast<int64_t>(c.p - 1) * c.q;
+            if (base < 0 || base + cnt > sched.pair_capacity) status = PRS_CFG_TOO_LARGE;
+        }
+        T result = CostTraits<T>::bad();
+        if (status == PRS_CFG_OK) result = run_bi<T, kSched>(c, slot, lay, sched, base, &status);
+        __syncthreads();
+        if (lane == 0) {
+            T *tg = static_cast<T *>(kSched ? sched.T_greedy : times.greedy);
+            int32_t *cs = kSched ? sched.cfg_status : times.cfg_status;
+            if (tg) tg[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();
+            if (cs) cs[i] = status;
+        }
+    }
+}
+
+template <typename T, bool kSched>
+static hipError_t launch_bi_t(const BiLaunch &L)
+{
+    hipLaunchKernelGGL((bi_kernel<T, kSched>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.model,
+                       L.times, L.sched, L.slots, L.slot_bytes, L.ticket);
+    return hipGetLastError();
+}
+
+hipError_t launch_bi(const BiLaunch &L)
+{
+    if (L.cost == PRS_COST_I64) return L.want_schedule ? launch_bi_t<int64_t, true>(L) : launch_bi_t<int64_t, false>(L);
+    return L.want_schedule ? launch_bi_t<double, true>(L) : launch_bi_t<double, false>(L);
+}
+
+}  // namespace prs

@@ -1,0 +1,192 @@
+// Device-side helpers shared by the gfx950 kernels: cost model, configuration
+// decoding and validation, wavefront (64-lane) primitives.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/prs.h"
+
+namespace prs {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- cost types
+template <typename T> struct CostTraits;
+template <> struct CostTraits<int64_t> {
+    static __device__ __forceinline__ int64_t inf() { return INT64_MAX; }
+    static __device__ __forceinline__ int64_t bad() { return -1; }
+    static __device__ __forceinline__ bool valid(int64_t v) { return v >= 0 && v < (INT64_C(1) << 62); }
+};
+template <> struct CostTraits<double> {
+    static __device__ __forceinline__ double inf() { return __builtin_huge_val(); }
+    static __device__ __forceinline__ double bad() { return __builtin_nan(""); }
+    static __device__ __forceinline__ bool valid(double v) { return v >= 0.0 && v < __builtin_huge_val(); }
+};
+
+// One configuration after decoding (Section 2: equi-segmentation; Section 5:
+// tcomm and tcomp of a segment).  Only two distinct segment sizes occur.
+template <typename T> struct Config {
+    int32_t p, q;          // processors, segments actually used
+    int64_t m, sz, sz_last;
+    T alpha, beta, gamma;
+    T c_full, g_full, c_last, g_last;
+    int32_t status;
+    __device__ __forceinline__ T c(int j) const { return j == q - 1 ? c_last : c_full; }
+    __device__ __forceinline__ T g(int j) const { return j == q - 1 ? g_last : g_full; }
+};
+
+struct ConfigArrays {
+    const int32_t *p, *q_req;
+    const int64_t *m;
+    const void *alpha, *beta, *gamma;
+};
+
+template <typename T>
+__device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_t i, int32_t p_max, int32_t q_max)
+{
+    Config<T> c;
+    c.p = a.p[i];
+    const int32_t q_req = a.q_req[i];
+    c.m = a.m[i];
+    c.alpha = static_cast<const T *>(a.alpha)[i];
+    c.beta = static_cast<const T *>(a.beta)[i];
+    c.gamma = static_cast<const T *>(a.gamma)[i];
+    c.status = PRS_CFG_OK;
+    c.q = 1; c.sz = 1; c.sz_last = 1;
+    c.c_full = c.g_full = c.c_last = c.g_last = 0;
+    if (c.p < 2 || q_req < 1 || c.m < 1 || c.m >= (INT64_C(1) << 62) || !CostTraits<T>::valid(c.alpha) ||
+        !CostTraits<T>::valid(c.beta) || !CostTraits<T>::valid(c.gamma)) {
+        c.status = PRS_CFG_BAD_PARAM;
+        return c;
+    }
+    if (c.p > p_max || q_req > q_max) { c.status = PRS_CFG_TOO_LARGE; return c; }
+    c.sz = (c.m + q_req - 1) / q_req;
+    const int64_t q = (c.m + c.sz - 1) / c.sz;
+    c.q = static_cast<int32_t>(q);
+    c.sz_last = c.m - (q - 1) * c.sz;
+    // products and sums are separate roundings (the library is built without FMA contraction)
+    const T bs = c.beta * static_cast<T>(c.sz);
+    c.c_full = c.alpha + bs;
+    c.g_full = c.gamma * static_cast<T>(c.sz);
+    const T bl = c.beta * static_cast<T>(c.sz_last);
+    c.c_last = c.alpha + bl;
+    c.g_last = c.gamma * static_cast<T>(c.sz_last);
+    if (!(c.c_full > 0) || !(c.c_last > 0) || !CostTraits<T>::valid(c.c_full) || !CostTraits<T>::valid(c.g_full))
+        c.status = PRS_CFG_BAD_PARAM;
+    return c;
+}
+
+__device__ __forceinline__ int32_t ceil_log2(int64_t v)
+{
+    return v <= 1 ? 0 : 64 - __builtin_clzll(static_cast<unsigned long long>(v - 1));
+}
+
+// ---------------------------------------------------------------- wavefront primitives
+__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }
+
+__device__ __forceinline__ uint64_t ballot64(bool pred) { return __ballot(pred ? 1 : 0); }
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int rank_below(uint64_t mask)
+{
+    return static_cast<int>(__builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u)));
+}
+
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int u = __shfl_up(v, o, kWave);
+        if (lane >= o) v += u;
+    }
+    return v;
+}
+
+template <typename T> __device__ __forceinline__ T wave_min(T v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const T u = __shfl_xor(v, o, kWave);
+        v = u < v ? u : v;
+    }
+    return v;
+}
+
+// keep the k lowest set bits of mask (k <= 0: none, k >= popcount: all)
+__device__ __forceinline__ uint64_t lowest_bits(uint64_t mask, int k)
+{
+    if (k <= 0) return 0;
+    if (k >= __popcll(mask)) return mask;
+    int pos = 0;                       // after the loop: index of the k-th set bit
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) {
+        const int cnt = __popcll((mask >> pos) & ((UINT64_C(1) << w) - 1));
+        if (cnt < k) { pos += w; k -= cnt; }
+    }
+    return mask & ((UINT64_C(2) << pos) - 1);
+}
+
+__device__ __forceinline__ uint64_t highest_bits(uint64_t mask, int k)
+{
+    if (k <= 0) return 0;
+    const int pc = __popcll(mask);
+    if (k >= pc) return mask;
+    return mask & ~lowest_bits(mask, pc - k);
+}
+
+// ---------------------------------------------------------------- closed forms
+// Tables I and III (standard algorithms), Table II / Figure 6 (bounds).
+struct TimesOut {
+    void *greedy, *binomial, *pipeline, *binary, *revopt;
+    double *butterfly, *lower_bound;
+    int32_t *q_eff, *cfg_status;
+};
+
+template <typename T>
+__device__ __forceinline__ void write_closed_forms(const TimesOut &o, int64_t i, const Config<T> &c, int model)
+{
+    if (c.status != PRS_CFG_OK) {
+        const T bad = CostTraits<T>::bad();
+        if (o.binomial) static_cast<T *>(o.binomial)[i] = bad;
+        if (o.pipeline) static_cast<T *>(o.pipeline)[i] = bad;
+        if (o.binary) static_cast<T *>(o.binary)[i] = bad;
+        if (o.revopt) static_cast<T *>(o.revopt)[i] = bad;
+        if (o.butterfly) o.butterfly[i] = __builtin_nan("");
+        if (o.lower_bound) o.lower_bound[i] = __builtin_nan("");
+        if (o.q_eff) o.q_eff[i] = -1;
+        return;
+    }
+    const int32_t L = ceil_log2(c.p), N = ceil_log2(static_cast<int64_t>(c.p) + 1);
+    const int64_t p = c.p, q = c.q;
+    const T r = (c.alpha + c.beta * static_cast<T>(c.sz)) + c.gamma * static_cast<T>(c.sz);
+    const T whole = (c.alpha + c.beta * static_cast<T>(c.m)) + c.gamma * static_cast<T>(c.m);
+    if (o.binomial) static_cast<T *>(o.binomial)[i] = static_cast<T>(L) * whole;
+    if (o.pipeline)
+        static_cast<T *>(o.pipeline)[i] = static_cast<T>(model == PRS_UNI ? (p - 1) + 2 * (q - 1) : p + q - 2) * r;
+    if (o.binary)
+        static_cast<T *>(o.binary)[i] =
+            static_cast<T>(model == PRS_UNI ? 2 * static_cast<int64_t>(N - 1) + 4 * (q - 1) : 2 * (N + q - 2)) * r;
+    if (o.revopt) static_cast<T *>(o.revopt)[i] = static_cast<T>(L + q - 1) * r;
+    const double Ld = static_cast<double>(L), fr = static_cast<double>(c.p - 1) / static_cast<double>(c.p);
+    const double md = static_cast<double>(c.m), al = static_cast<double>(c.alpha), be = static_cast<double>(c.beta),
+                 ga = static_cast<double>(c.gamma);
+    if (o.butterfly) o.butterfly[i] = ((2.0 * Ld) * al + (2.0 * fr) * (be * md)) + fr * (ga * md);
+    if (o.lower_bound) {
+        const double bw = (model == PRS_UNI && c.p > 2) ? 2.0 * (md * be) : md * be;
+        o.lower_bound[i] = (Ld * al + bw) + fr * (md * ga);
+    }
+    if (o.q_eff) o.q_eff[i] = c.q;
+}
+
+}  // namespace prs

@@ -1,0 +1,70 @@
+// Host-side launch descriptors shared by the API file and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "prs_device.h"
+
+namespace prs {
+
+struct SchedOut {
+    const int64_t *pair_offset;
+    int64_t pair_capacity;
+    int32_t *src, *dst, *seg;
+    void *tstart;
+    void *T_greedy;
+    int32_t *cfg_status;
+};
+
+struct UniLaunch {
+    ConfigArrays cfg;
+    int64_t n;
+    int32_t p_max, q_max;
+    int model, cost;
+    bool want_schedule;
+    TimesOut times;
+    SchedOut sched;
+    char *slots;
+    size_t slot_bytes;
+    unsigned long long *ticket;
+    int grid;
+    hipStream_t stream;
+};
+
+typedef UniLaunch BiLaunch;   // same fields; slots sized by bi_slot_bytes
+
+size_t uni_slot_bytes(bool sched, int32_t p_max);
+size_t bi_slot_bytes(int32_t p_max, int32_t q_max);
+hipError_t launch_uni(const UniLaunch &L);
+hipError_t launch_bi(const BiLaunch &L);
+
+struct ReplayLaunch {
+    int32_t p, q;
+    const int64_t *seg_elem_offset;
+    const int32_t *src, *dst, *seg;
+    int64_t n_pairs;
+    const void *in;
+    int64_t stride_elems, n_elems;
+    int dtype;
+    void *out;
+    int32_t *status;
+    char *workspace;
+    hipStream_t stream;
+};
+size_t replay_workspace_bytes(int32_t p, int32_t q);
+hipError_t launch_replay(const ReplayLaunch &L);
+
+struct OffsetsLaunch {
+    ConfigArrays cfg;
+    int64_t n;
+    int32_t p_max, q_max;
+    int cost;
+    int64_t *pair_offset;
+    hipStream_t stream;
+};
+hipError_t launch_offsets(const OffsetsLaunch &L);
+hipError_t launch_clear(unsigned long long *words, int count, hipStream_t stream);
+
+}  // namespace prs

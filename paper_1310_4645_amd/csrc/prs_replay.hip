@@ -1,0 +1,307 @@
+// Replay of a reduction schedule on data (Lowery & Langou, Section 4: the
+// receiver of a pair combines the received segment into its own) on gfx950.
+//
+// Applying the pairs one after the other would move every partial result
+// through memory once per pair.  Instead, per segment the pairs form an
+// in-tree rooted at processor 0; the value the root ends with is
+//     e(i) = (((own_i + e(c_1)) + e(c_2)) + ... )          c_k = k-th sender to i
+// evaluated recursively.  A small kernel turns each segment's tree into a
+// linear program over the p input buffers (each read exactly once), and the
+// streaming kernel evaluates that program per element with a short stack of
+// partial sums held in registers.  Because a + b == b + a bit for bit, the
+// first child's subtree is evaluated in place before own_i is added, so only
+// later children that have children of their own need a stack slot.
+//
+// Program entry for position k of segment s: prog[s*p + k] =
+//     processor | push << 20 | npop << 21
+// "load the processor's element; if push, save the running sum and start a new
+// one from the loaded value, else add it to the running sum; then npop times
+// add the running sum into the last saved one".
+#include "prs_device.h"
+#include "prs_launch.h"
+
+namespace prs {
+
+constexpr int kReplayThreads = 256;
+constexpr int kBuildThreads = 256;
+constexpr int kStackDepth = 24;      // saved partial sums per element
+constexpr int kPrefetch = 8;         // loads in flight per lane
+
+struct ReplayWs {
+    int64_t *offsets;      // q+1
+    uint32_t *prog;        // q*p
+    int32_t *tmp;          // q * 8 * p scratch of the builder
+    int32_t *flags;        // [0] invalid, [1] too deep
+};
+
+__host__ __device__ inline size_t rp_align(size_t v) { return (v + 255) / 256 * 256; }
+
+size_t replay_workspace_bytes(int32_t p, int32_t q)
+{
+    const size_t P = static_cast<size_t>(p), Q = static_cast<size_t>(q);
+    return rp_align((Q + 1) * 8) + rp_align(Q * P * 4) + rp_align(Q * P * 4 * 8) + 256;
+}
+
+static ReplayWs carve_replay(char *ws, int32_t p, int32_t q)
+{
+    const size_t P = static_cast<size_t>(p), Q = static_cast<size_t>(q);
+    ReplayWs w;
+    w.offsets = reinterpret_cast<int64_t *>(ws); ws += rp_align((Q + 1) * 8);
+    w.prog = reinterpret_cast<uint32_t *>(ws); ws += rp_align(Q * P * 4);
+    w.tmp = reinterpret_cast<int32_t *>(ws); ws += rp_align(Q * P * 4 * 8);
+    w.flags = reinterpret_cast<int32_t *>(ws);
+    return w;
+}
+
+__global__ void replay_clear_flags(int32_t *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
+
+// Segment offsets travel as kernel arguments, a chunk at a time: no host-to-device copy is enqueued.
+constexpr int kOffsetChunk = 256;
+struct OffsetChunk { int64_t v[kOffsetChunk]; };
+__global__ void replay_store_offsets(OffsetChunk chunk, int base, int count, int64_t *dst)
+{
+    const int i = threadIdx.x;
+    if (i < count) dst[base + i] = chunk.v[i];
+}
+
+// One block per segment: tree of the segment's pairs -> linear program.
+__global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t q, const int32_t *src, const int32_t *dst,
+                                                              const int32_t *seg, int64_t n_pairs, uint32_t *prog,
+                                                              int32_t *tmp, int32_t *flags)
+{
+    const int k = blockIdx.x, tid = threadIdx.x;
+    int32_t *base = tmp + static_cast<size_t>(k) * 8 * p;
+    int32_t *parent = base, *ord = base + p, *ci = base + 2 * p, *nchild = base + 3 * p, *size = base + 4 * p,
+            *offStart = base + 5 * p, *fchild = base + 6 * p, *start = base + 7 * p;
+    __shared__ int s_bad, s_count;
+    if (tid == 0) { s_bad = 0; s_count = 0; }
+    for (int i = tid; i < p; i += kBuildThreads) { parent[i] = -1; ord[i] = -1; nchild[i] = 0; size[i] = 1; fchild[i] = -1; }
+    __syncthreads();
+    // 1. who sends to whom, and when (position in emission order)
+    for (int64_t e = tid; e < n_pairs; e += kBuildThreads) {
+        if (seg[e] != k) { if (seg[e] < 0 || seg[e] >= q) s_bad = 1; continue; }
+        const int32_t s = src[e], d = dst[e];
+        if (s <= 0 || s >= p || d < 0 || d >= p || s == d) { s_bad = 1; continue; }
+        if (atomicCAS(&parent[s], -1, d) != -1) { s_bad = 1; continue; }      // sends the segment twice
+        ord[s] = static_cast<int32_t>(e);
+        atomicAdd(&nchild[d], 1);
+        atomicAdd(&s_count, 1);
+    }
+    __syncthreads();
+    if (s_count != p - 1) s_bad = 1;
+    __syncthreads();
+    // 2. position among the senders to the same receiver; a processor sends after all it receives
+    for (int i = tid; i < p; i += kBuildThreads) {
+        if (i == 0 || parent[i] < 0) { ci[i] = 0; continue; }
+        const int32_t par = parent[i], oi = ord[i];
+        int32_t c = 0;
+        for (int s = 1; s < p; ++s) {
+            if (parent[s] == par && ord[s] < oi) ++c;
+            if (parent[s] == i && ord[s] > oi) s_bad = 1;
+        }
+        ci[i] = c;
+        if (c == 0) fchild[par] = i;
+    }
+    __syncthreads();
+    if (s_bad) { if (tid == 0) flags[0] = 1; return; }
+    // 3. subtree sizes: every processor counts itself into each of its ancestors (ord grows along
+    //    the way to the root, so the walk ends)
+    for (int i = tid; i < p; i += kBuildThreads)
+        for (int a = parent[i], hops = 0; a >= 0 && hops < p; a = parent[a], ++hops) atomicAdd(&size[a], 1);
+    __syncthreads();
+    // 4. where a child's part starts relative to its parent's part: the first child starts with
+    //    the parent; later ones after the first child's part, the parent itself and the earlier siblings
+    for (int i = tid; i < p; i += kBuildThreads) {
+        int32_t off = 0;
+        if (i != 0 && ci[i] > 0) {
+            off = 1;
+            const int32_t par = parent[i], me = ci[i];
+            for (int s = 1; s < p; ++s)
+                if (parent[s] == par && ci[s] < me) off += size[s];
+        }
+        offStart[i] = off;
+    }
+    __syncthreads();
+    for (int i = tid; i < p; i += kBuildThreads) {
+        int32_t st = 0;
+        for (int a = i, hops = 0; a > 0 && hops < p; a = parent[a], ++hops) st += offStart[a];
+        start[i] = st;
+    }
+    __syncthreads();
+    // 5. one program entry per processor
+    int deepest = 0;
+    for (int i = tid; i < p; i += kBuildThreads) {
+        const int32_t pos = start[i] + (nchild[i] > 0 ? size[fchild[i]] : 0);
+        int push = 0;
+        if (nchild[i] == 0) {                       // a leaf that opens the part of a saved subtree (or of the root)
+            int a = i;
+            for (int hops = 0; a != 0 && ci[a] == 0 && hops < p; ++hops) a = parent[a];
+            push = (a == 0 || a != i) ? 1 : 0;
+        }
+        int npop = 0, depth = 0;
+        for (int a = i, hops = 0; a > 0 && hops < p; a = parent[a], ++hops) {
+            const bool saved = ci[a] > 0 && nchild[a] > 0;
+            if (saved) {
+                ++depth;
+                if (start[a] + size[a] - 1 == pos) ++npop;
+            }
+        }
+        if (depth > deepest) deepest = depth;
+        prog[static_cast<size_t>(k) * p + pos] = static_cast<uint32_t>(i) | (static_cast<uint32_t>(push) << 20) |
+                                                 (static_cast<uint32_t>(npop) << 21);
+    }
+    if (deepest + 1 > kStackDepth) flags[1] = 1;
+}
+
+template <typename E> struct Vec4 { E v[4]; };
+
+template <typename E> __device__ __forceinline__ E add1(E a, E b);
+template <> __device__ __forceinline__ float add1<float>(float a, float b) { return a + b; }
+template <> __device__ __forceinline__ int32_t add1<int32_t>(int32_t a, int32_t b)
+{
+    return static_cast<int32_t>(static_cast<uint32_t>(a) + static_cast<uint32_t>(b));
+}
+
+template <typename E, int VEC> struct Acc {
+    E v[VEC];
+    __device__ __forceinline__ void add(const Acc &o)
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = add1<E>(v[i], o.v[i]);
+    }
+};
+
+template <typename E, int VEC>
+__device__ __forceinline__ Acc<E, VEC> load_elems(const E *ptr, int nvalid)
+{
+    Acc<E, VEC> a;
+    if (VEC == 4 && nvalid == 4) {
+        const float4 f = *reinterpret_cast<const float4 *>(ptr);
+        const E *fe = reinterpret_cast<const E *>(&f);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) a.v[i] = fe[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) a.v[i] = i < nvalid ? ptr[i] : E(0);
+    }
+    return a;
+}
+
+// stack of saved partial sums in registers; sp is uniform over the wavefront
+#define PRS_STACK_CASES(OP) \
+    OP(0) OP(1) OP(2) OP(3) OP(4) OP(5) OP(6) OP(7) OP(8) OP(9) OP(10) OP(11) OP(12) OP(13) OP(14) OP(15) \
+    OP(16) OP(17) OP(18) OP(19) OP(20) OP(21) OP(22) OP(23)
+
+template <typename E, int VEC>
+__global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const int64_t *offsets, const uint32_t *prog,
+                                                                const E *in, int64_t stride, E *out, const int32_t *flags)
+{
+    if (flags[0] | flags[1]) return;
+    const int k = blockIdx.y;
+    const int64_t lo = offsets[k], hi = offsets[k + 1];
+    const int64_t e0 = lo + (static_cast<int64_t>(blockIdx.x) * kReplayThreads + threadIdx.x) * VEC;
+    if (e0 >= hi) return;
+    const int nvalid = hi - e0 >= VEC ? VEC : static_cast<int>(hi - e0);
+    const uint32_t *pg = prog + static_cast<size_t>(k) * p;
+    Acc<E, VEC> acc;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc.v[i] = E(0);
+    Acc<E, VEC> stk[kStackDepth];
+    int sp = 0;
+    for (int base = 0; base < p; base += kPrefetch) {
+        uint32_t ent[kPrefetch];
+        Acc<E, VEC> val[kPrefetch];
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) ent[u] = base + u < p ? pg[base + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u)
+            if (base + u < p) val[u] = load_elems<E, VEC>(in + static_cast<int64_t>(ent[u] & 0xFFFFFu) * stride + e0, nvalid);
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+            if (base + u >= p) break;
+            if ((ent[u] >> 20) & 1u) {
+#define PRS_PUSH(d) case d: stk[d] = acc; break;
+                switch (sp) { PRS_STACK_CASES(PRS_PUSH) default: break; }
+#undef PRS_PUSH
+                ++sp;
+                acc = val[u];
+            } else {
+                acc.add(val[u]);
+            }
+            for (int np = static_cast<int>(ent[u] >> 21); np > 0; --np) {
+                --sp;
+                Acc<E, VEC> top;
+#define PRS_POP(d) case d: top = stk[d]; break;
+                switch (sp) { PRS_STACK_CASES(PRS_POP) default: top = acc; break; }
+#undef PRS_POP
+                top.add(acc);            // saved partial sum + finished subtree
+                acc = top;
+            }
+        }
+    }
+    if (VEC == 4 && nvalid == 4) {
+        float4 f;
+        E *fe = reinterpret_cast<E *>(&f);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) fe[i] = acc.v[i];
+        *reinterpret_cast<float4 *>(out + e0) = f;
+    } else {
+        for (int i = 0; i < nvalid; ++i) out[e0 + i] = acc.v[i];
+    }
+}
+
+__global__ void replay_write_status(const int32_t *flags, int32_t *status)
+{
+    if (threadIdx.x == 0 && status) *status = flags[0] ? 1 : (flags[1] ? 2 : 0);
+}
+
+template <typename E>
+static hipError_t launch_replay_t(const ReplayLaunch &L, const ReplayWs &w, int64_t max_len, bool vec_ok)
+{
+    const E *in = static_cast<const E *>(L.in);
+    E *out = static_cast<E *>(L.out);
+    if (max_len > 0) {
+        if (vec_ok) {
+            const int64_t groups = (max_len + 3) / 4;
+            dim3 grid(static_cast<unsigned>((groups + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
+            hipLaunchKernelGGL((replay_kernel<E, 4>), grid, dim3(kReplayThreads), 0, L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+        } else {
+            dim3 grid(static_cast<unsigned>((max_len + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
+            hipLaunchKernelGGL((replay_kernel<E, 1>), grid, dim3(kReplayThreads), 0, L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+        }
+    }
+    return hipGetLastError();
+}
+
+// L.seg_elem_offset is a host array here (validated by the caller).
+hipError_t launch_replay(const ReplayLaunch &L)
+{
+    const ReplayWs w = carve_replay(L.workspace, L.p, L.q);
+    int64_t max_len = 0;
+    bool vec_ok = (L.stride_elems % 4 == 0) && (reinterpret_cast<uintptr_t>(L.in) % 16 == 0) &&
+                  (reinterpret_cast<uintptr_t>(L.out) % 16 == 0);
+    for (int k = 0; k < L.q; ++k) {
+        const int64_t len = L.seg_elem_offset[k + 1] - L.seg_elem_offset[k];
+        if (len > max_len) max_len = len;
+        if (L.seg_elem_offset[k] % 4 != 0) vec_ok = false;
+    }
+    hipError_t err = hipSuccess;
+    for (int base = 0; base < L.q + 1; base += kOffsetChunk) {
+        OffsetChunk chunk;
+        const int count = L.q + 1 - base < kOffsetChunk ? L.q + 1 - base : kOffsetChunk;
+        for (int i = 0; i < count; ++i) chunk.v[i] = L.seg_elem_offset[base + i];
+        hipLaunchKernelGGL(replay_store_offsets, dim3(1), dim3(kOffsetChunk), 0, L.stream, chunk, base, count, w.offsets);
+    }
+    hipLaunchKernelGGL(replay_clear_flags, dim3(1), dim3(64), 0, L.stream, w.flags);
+    hipLaunchKernelGGL(replay_build, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), 0, L.stream, L.p, L.q, L.src, L.dst,
+                       L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    err = L.dtype == PRS_F32 ? launch_replay_t<float>(L, w, max_len, vec_ok) : launch_replay_t<int32_t>(L, w, max_len, vec_ok);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(replay_write_status, dim3(1), dim3(64), 0, L.stream, w.flags, L.status);
+    return hipGetLastError();
+}
+
+}  // namespace prs

@@ -1,0 +1,341 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Integer results, schedules and replay must match
+bit for bit; fp64 times within 1e-12 relative."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import pytest
+
+import oracle as O
+import prs_inputs
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-12
+
+
+@pytest.fixture(scope="module")
+def prs():
+    import torch
+    import paper_1310_4645_amd as lib
+    assert torch.cuda.is_available()
+    lib.load_library()
+    return lib
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _np(t):
+    return t.cpu().numpy()
+
+
+def _rel_ok(got, ref, rel=REL):
+    return np.all(np.abs(got - ref) <= rel * np.abs(ref))
+
+
+def _check_times(got, ref: O.BatchResult, exact):
+    for key, r in (("greedy", ref.T_greedy), ("binomial", ref.T_binomial), ("pipeline", ref.T_pipeline),
+                   ("binary", ref.T_binary), ("revopt", ref.T_revopt)):
+        g = _np(got[key])
+        if exact:
+            assert np.array_equal(g, r), key
+        else:
+            assert _rel_ok(g, r), (key, np.max(np.abs(g - r) / np.abs(r)))
+    assert _rel_ok(_np(got["butterfly"]), ref.T_butterfly)
+    assert _rel_ok(_np(got["lower_bound"]), ref.T_lower_bound)
+    assert np.array_equal(_np(got["q_eff"]), ref.q_eff)
+    assert np.array_equal(_np(got["cfg_status"]), ref.status)
+
+
+def _oracle_schedules(host, model):
+    out = []
+    for i in range(len(host)):
+        sizes = O.equi_sizes(int(host.m[i]), int(host.q_req[i]))
+        a, b, g = host.alpha[i].item(), host.beta[i].item(), host.gamma[i].item()
+        fn = O.uni_greedy if model == O.UNI else O.bi_greedy
+        kw = {} if model == O.UNI else {"mode": O.MODE_EVENT | O.MODE_PRUNE}
+        out.append(fn(int(host.p[i]), sizes, a, b, g, host.cost, **kw))
+    return out
+
+
+def _check_schedules(prs, host, model, p_max, q_max, exact_t=True):
+    dev = prs.DeviceConfigs.from_host(host)
+    off = prs.prs_pair_offsets(dev, p_max, q_max)
+    _sync()
+    offh = _np(off)
+    refs = _oracle_schedules(host, model)
+    want_off = np.concatenate([[0], np.cumsum([len(r.src) for r in refs])])
+    assert np.array_equal(offh, want_off)
+    sch = prs.greedy_schedule_batch(dev, model, p_max, q_max, off, int(offh[-1]))
+    _sync()
+    src, dst, seg, t, T = (_np(sch[k]) for k in ("src", "dst", "seg", "t_start", "T_greedy"))
+    assert np.all(_np(sch["cfg_status"]) == 0)
+    for i, r in enumerate(refs):
+        a, b = offh[i], offh[i + 1]
+        ctx = (i, int(host.p[i]), int(host.q_req[i]), int(host.m[i]))
+        assert np.array_equal(src[a:b], r.src), ("src", ctx)
+        assert np.array_equal(dst[a:b], r.dst), ("dst", ctx)
+        assert np.array_equal(seg[a:b], r.seg), ("seg", ctx)
+        if exact_t:
+            assert np.array_equal(t[a:b], r.t), ("t", ctx)
+            assert T[i] == r.T, ("T", ctx)
+        else:
+            assert _rel_ok(t[a:b], r.t) and abs(T[i] - r.T) <= REL * abs(r.T), ("t", ctx)
+
+
+# --------------------------------------------------------------------------- tiny sweep, integer costs
+@pytest.mark.parametrize("model", [0, 1])
+def test_tiny_sweep_times_bit_exact(prs, model):
+    host = prs_inputs.tiny_sweep()
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, model, 16, 8)
+    _sync()
+    _check_times(got, O.simulate_batch(host, model), exact=True)
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_tiny_sweep_schedules_bit_exact(prs, model):
+    _check_schedules(prs, prs_inputs.tiny_sweep(), model, 16, 8)
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_integer_costs_ragged_segments_and_larger_p(prs, model):
+    rng = np.random.default_rng(2024 + model)
+    n = 160
+    p = rng.integers(2, 200, n).astype(np.int32)
+    p[:8] = [2, 3, 63, 64, 65, 127, 128, 129]                  # word and tile boundaries
+    m = rng.integers(1, 300, n).astype(np.int64)
+    q = rng.integers(1, 24, n).astype(np.int32)
+    host = prs_inputs.SweepConfigs(p, q, m, rng.integers(0, 12, n).astype(np.int64), rng.integers(0, 4, n).astype(np.int64),
+                                   rng.integers(0, 4, n).astype(np.int64), "i64")
+    host.alpha[host.beta == 0] += 1                                 # tcomm > 0
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, model, 256, 32)
+    _sync()
+    _check_times(got, O.simulate_batch(host, model), exact=True)
+    _check_schedules(prs, host, model, 256, 32)
+
+
+# --------------------------------------------------------------------------- fp64 sweeps
+def _fast_subset(host, budget, limit):
+    """indices of configurations the plain oracle finishes quickly (cost ~ p^2 q)."""
+    work = host.p.astype(np.float64) ** 2 * host.q_req
+    idx = np.nonzero(work <= budget)[0][:limit]
+    return idx
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_fp64_sweep_sample_times(prs, model):
+    full = prs_inputs.uni_sweep(4000)
+    idx = _fast_subset(full, 4e6 if model == 0 else 3e5, 500)
+    big = np.argsort(-(full.p.astype(np.float64) * full.q_req))[:3]             # a few heavy ones too
+    host = full.take(np.concatenate([idx, big]))
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, model, 1024, 512)
+    _sync()
+    ref = O.simulate_batch(host, model)
+    _check_times(got, ref, exact=False)
+    # the arithmetic is the same sequence of roundings on both sides
+    assert np.array_equal(_np(got["greedy"]), ref.T_greedy)
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_fp64_sweep_sample_schedules(prs, model):
+    full = prs_inputs.uni_sweep(3000)
+    idx = _fast_subset(full, 6e5 if model == 0 else 1e5, 120)
+    _check_schedules(prs, full.take(idx), model, 1024, 512)
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_fp64_rounding_ties(prs, model):
+    # costs chosen so that sums produced at different times round to the same double
+    n = 69
+    p = np.arange(2, 2 + n).astype(np.int32)
+    cases = [(1.0, 0.0, 2.0 ** -52), (1.0, 0.0, 2.0 ** -53), (0.75, 2.0 ** -54, 2.0 ** -51), (1.0, 2.0 ** -30, 0.0)]
+    for al, be, ga in cases:
+        host = prs_inputs.SweepConfigs(p, np.full(n, 5, np.int32), np.full(n, 13, np.int64), np.full(n, al),
+                                       np.full(n, be), np.full(n, ga), "f64")
+        dev = prs.DeviceConfigs.from_host(host)
+        got = prs.simulate_completion_batch(dev, model, 128, 8)
+        _sync()
+        ref = O.simulate_batch(host, model)
+        assert np.array_equal(_np(got["greedy"]), ref.T_greedy), (al, be, ga)
+        _check_schedules(prs, host, model, 128, 8)
+
+
+def test_invalid_configurations_are_reported_not_fatal(prs):
+    p = np.array([1, 8, 8, 8, 8, 300, 8, 8], np.int32)
+    q = np.array([2, 0, 2, 2, 2, 2, 99, 3], np.int32)
+    m = np.array([4, 4, 0, 4, 4, 4, 400, 6], np.int64)
+    al = np.array([1.0, 1.0, 1.0, -1.0, float("nan"), 1.0, 1.0, 2.0])
+    host = prs_inputs.SweepConfigs(p, q, m, al, np.ones(8), np.ones(8), "f64")
+    dev = prs.DeviceConfigs.from_host(host)
+    for model in (0, 1):
+        got = prs.simulate_completion_batch(dev, model, 64, 16)
+        _sync()
+        st = _np(got["cfg_status"])
+        assert list(st) == [1, 1, 1, 1, 1, 2, 2, 0]
+        g = _np(got["greedy"])
+        assert np.all(np.isnan(g[:7]))
+        sizes = O.equi_sizes(6, 3)
+        want = (O.uni_greedy if model == 0 else O.bi_greedy)(8, sizes, 2.0, 1.0, 1.0, "f64").T
+        assert g[7] == want
+    off = prs.prs_pair_offsets(dev, 64, 16)
+    _sync()
+    assert list(_np(off)) == [0] * 8 + [21]
+    # capacity too small for the only valid configuration
+    sch = prs.greedy_schedule_batch(dev, 0, 64, 16, off, 20)
+    _sync()
+    assert _np(sch["cfg_status"])[7] == 2
+    # call-level errors: nothing is enqueued
+    with pytest.raises(prs.PrsError):
+        prs.simulate_completion_batch(dev, 7, 64, 16)
+    with pytest.raises(prs.PrsError):
+        prs.simulate_completion_batch(dev, 0, 1, 16)
+
+
+def test_empty_batch(prs):
+    host = prs_inputs.tiny_sweep().take(np.arange(0))
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, 0, 16, 8)
+    _sync()
+    assert got["greedy"].numel() == 0
+
+
+# --------------------------------------------------------------------------- full-size sweeps
+@pytest.mark.parametrize("model", [0, 1])
+def test_full_sweep_invariants_and_samples(prs, model):
+    """The 100,000-configuration sweep in the launch shape the benchmark times: sampled configurations
+    against the oracle, every configuration against what holds at any size."""
+    host = prs_inputs.uni_sweep()
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, model, 1024, 512)
+    _sync()
+    T = _np(got["greedy"])
+    assert np.all(_np(got["cfg_status"]) == 0) and np.all(np.isfinite(T))
+    q = _np(got["q_eff"]).astype(np.int64)
+    sz = -(-host.m // host.q_req)
+    assert np.array_equal(q, -(-host.m // sz))
+    L = np.ceil(np.log2(host.p)).astype(np.int64)
+    r = (host.alpha + host.beta * sz) + host.gamma * sz
+    if model == 0:
+        # Theorem 1: no slower than the in-order pipeline and binary trees; Table II bounds
+        assert np.all(T <= _np(got["pipeline"]) * (1 + 1e-12))
+        assert np.all(T <= _np(got["binary"]) * (1 + 1e-12))
+        assert np.all(T >= L * host.alpha)
+        one = q == 1                                            # a single segment is the binomial tree
+        assert _rel_ok(T[one], _np(got["binomial"])[one])
+    else:
+        # Section 6.2: equals the reversed optimal broadcast whenever all segments are equal
+        eq = host.m % sz == 0
+        assert eq.sum() > 1000
+        assert _rel_ok(T[eq], ((L + q - 1) * r)[eq], 1e-11)
+        assert np.all(T >= L * host.alpha)
+    rng = np.random.default_rng(99)
+    work = host.p.astype(np.float64) ** 2 * host.q_req
+    cand = np.nonzero(work <= (2e7 if model == 0 else 1e6))[0]
+    idx = np.sort(rng.choice(cand, 300, replace=False))
+    ref = O.simulate_batch(host, model, index=idx)
+    assert np.array_equal(T[idx], ref.T_greedy)
+    assert _rel_ok(_np(got["butterfly"])[idx], ref.T_butterfly) and _rel_ok(_np(got["revopt"])[idx], ref.T_revopt)
+
+
+@pytest.mark.parametrize("model", [0, 1])
+def test_large_p_sample(prs, model):
+    full = prs_inputs.large_p_sweep(2000)
+    work = full.p.astype(np.float64) ** 2 * full.q_req
+    idx = np.argsort(work)[: (6 if model == 0 else 3)]
+    host = full.take(idx)
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, model, 65536, 4096)
+    _sync()
+    ref = O.simulate_batch(host, model)
+    assert np.array_equal(_np(got["greedy"]), ref.T_greedy)
+    assert np.all(_np(got["cfg_status"]) == 0)
+
+
+# --------------------------------------------------------------------------- replay
+def _replay_case(prs, p, sizes, model, seg_off, dtype, cost=("i64", 2, 1, 1), strided=False):
+    import torch
+    cst, a, b, g = cost
+    s = (O.uni_greedy if model == 0 else O.bi_greedy)(p, sizes, a, b, g, cst)
+    n = int(seg_off[-1])
+    buf = prs_inputs.replay_buffers(p, n, dtype)
+    want = O.replay(p, seg_off, s.src, s.dst, s.seg, buf)
+    dbuf = torch.from_numpy(buf).cuda()
+    if strided:
+        wide = torch.zeros((p, n + 3), dtype=dbuf.dtype, device="cuda")
+        wide[:, :n] = dbuf
+        dbuf = wide[:, :n]
+    out, st = prs.replay_reduction(p, len(sizes), seg_off, torch.from_numpy(s.src).cuda(), torch.from_numpy(s.dst).cuda(),
+                                   torch.from_numpy(s.seg).cuda(), dbuf)
+    _sync()
+    assert int(st.item()) == 0
+    assert _np(out).tobytes() == want.tobytes(), (p, model, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32"])
+@pytest.mark.parametrize("model", [0, 1])
+def test_replay_small_ragged(prs, model, dtype):
+    q = 5
+    off = np.array([0, 1000, 2000, 3000, 4000, 4321], np.int64)          # aligned starts, ragged end
+    _replay_case(prs, 23, [4] * 4 + [2], model, off, dtype)
+    off = np.array([0, 37, 74, 111, 148, 150], np.int64)                 # unaligned starts: scalar path
+    _replay_case(prs, 37, [4] * 4 + [1], model, off, dtype)
+    _replay_case(prs, 2, [3], model, np.array([0, 5], np.int64), dtype)
+    _replay_case(prs, 130, [4] * q, model, np.arange(q + 1, dtype=np.int64) * 2048, dtype, strided=True)
+
+
+def test_replay_rejects_a_schedule_that_is_not_a_tree(prs):
+    import torch
+    p, q = 4, 1
+    src = torch.tensor([1, 1, 3], dtype=torch.int32).cuda()             # processor 1 sends twice, 2 never
+    dst = torch.tensor([0, 2, 0], dtype=torch.int32).cuda()
+    seg = torch.zeros(3, dtype=torch.int32).cuda()
+    buf = torch.ones((p, 8), dtype=torch.float32).cuda()
+    out, st = prs.replay_reduction(p, q, np.array([0, 8], np.int64), src, dst, seg, buf)
+    _sync()
+    assert int(st.item()) == 1
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32"])
+def test_replay_full_size_sampled_columns(prs, dtype):
+    """p = 256, 64 segments, 2^22 elements per buffer: the benchmark's replay.  Buffers are drawn on
+    the device; the oracle replays sampled element columns copied back from it."""
+    import torch
+    host = prs_inputs.replay_config()
+    p, q, n = 256, 64, 1 << 22
+    sizes = O.equi_sizes(int(host.m[0]), q)
+    s = O.uni_greedy(p, sizes, 1e-5, 1e-9, 1e-10, "f64")
+    gen = torch.Generator(device="cuda").manual_seed(prs_inputs.SEED_REPLAY)
+    if dtype == "i32":
+        buf = torch.randint(-2 ** 20, 2 ** 20 + 1, (p, n), dtype=torch.int32, device="cuda", generator=gen)
+    else:
+        buf = torch.randn((p, n), dtype=torch.float32, device="cuda", generator=gen)
+    seg_off = np.arange(q + 1, dtype=np.int64) * (n // q)
+    dev = prs.DeviceConfigs.from_host(host)
+    off = prs.prs_pair_offsets(dev, 256, 64)
+    sch = prs.greedy_schedule_batch(dev, 0, 256, 64, off, (p - 1) * q)
+    _sync()
+    assert np.array_equal(_np(sch["src"]), s.src) and np.array_equal(_np(sch["dst"]), s.dst)
+    out, st = prs.replay_reduction(p, q, seg_off, sch["src"], sch["dst"], sch["seg"], buf)
+    _sync()
+    assert int(st.item()) == 0
+    rng = np.random.default_rng(7)
+    cols = np.unique(np.concatenate([rng.integers(0, n, 3000), seg_off[:-1], seg_off[1:] - 1]))
+    sub = buf[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    col_seg = np.searchsorted(seg_off, cols, side="right") - 1
+    # replay the sampled columns: one pseudo-segment per original segment, columns grouped by it
+    order = np.argsort(col_seg, kind="stable")
+    sub = np.ascontiguousarray(sub[:, order])
+    sub_off = np.concatenate([[0], np.cumsum(np.bincount(col_seg, minlength=q))]).astype(np.int64)
+    want = O.replay(p, sub_off, s.src, s.dst, s.seg, sub)
+    got = _np(out)[cols[order]]
+    assert got.tobytes() == want.tobytes()
+    if dtype == "i32":
+        assert np.array_equal(got, sub.sum(axis=0, dtype=np.int64).astype(np.int32))

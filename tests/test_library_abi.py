@@ -1,0 +1,46 @@
+"""CPU-side checks of the boundary: the shared library loads without a GPU and
+exports every function that include/prs.h declares; host-only entry points
+behave."""
+from __future__ import annotations
+
+import os
+import re
+
+import paper_1310_4645_amd as prs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "prs.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|size_t)\s+(\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"simulate_completion_batch", "greedy_schedule_batch", "replay_reduction"} <= set(names)
+    lib = prs.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(prs.binding.EXPORTS) == names
+    assert lib.prs_abi_version() == 1
+
+
+def test_workspace_sizes_are_monotone_and_bounded():
+    w = prs.prs_workspace_bytes
+    assert w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 64, 8) < w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 1024, 8)
+    assert w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10, 64, 8) < w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10, 64, 512)
+    assert w(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI, 1, 10, 64, 8) > w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 64, 8)
+    assert w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10_000, 65536, 4096) <= 20 << 30
+    assert w(prs.PRS_CALL_REPLAY, 0, 0, 1, 256, 64) > 256 * 64 * 4
+    assert w(99, 0, 0, 1, 256, 64) == 0 and w(0, 0, 0, -1, 256, 64) == 0
+
+
+def test_product_path_has_no_oracle_dependency():
+    pkg = os.path.join(ROOT, "paper_1310_4645_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src and "prs_oracle" not in src, f
