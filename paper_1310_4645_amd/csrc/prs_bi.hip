@@ -227,18 +227,13 @@ __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, 
                                                    TimesOut times, SchedOut sched, char *slots, size_t slot_bytes,
                                                    unsigned long long *ticket)
 {
-    __shared__ unsigned long long s_next;
     const int lane = lane_id();
     const BiLayout lay = bi_layout(p_max, q_max);
     char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
     for (;;) {
-        if (lane == 0) s_next = atomicAdd(ticket, 1ULL);
-        __syncthreads();
-        const int64_t i = static_cast<int64_t>(s_next);
-        __syncthreads();
+        const int64_t i = next_ticket(ticket);
         if (i >= n) break;
         Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
-        if (!kSched && lane == 0) write_closed_forms<T>(times, i, c, model);
         int32_t status = c.status;
         int64_t base = 0;
         if (kSched && status == PRS_CFG_OK) {
@@ -249,7 +244,8 @@ __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, 
         T result = CostTraits<T>::bad();
         if (status == PRS_CFG_OK) result = run_bi<T, kSched>(c, slot, lay, sched, base, &status);
         __syncthreads();
-        if (lane == 0) {
+        if (lane == 0) {                  // the only lane-dependent branch of the loop body
+            if (!kSched) write_closed_forms<T>(times, i, c, model);
             T *tg = static_cast<T *>(kSched ? sched.T_greedy : times.greedy);
             int32_t *cs = kSched ? sched.cfg_status : times.cfg_status;
             if (tg) tg[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();

@@ -123,6 +123,17 @@ template <typename T> __device__ __forceinline__ T wave_min(T v)
     return v;
 }
 
+// Next index of a work counter, the same value in all 64 lanes.  Every lane issues the atomic (lane 0
+// adds one, the others zero) and the result is broadcast with a cross-lane read: no lane-dependent
+// branch, so no lane can run ahead of the others into the next loop iteration.
+__device__ __forceinline__ int64_t next_ticket(unsigned long long *counter)
+{
+    const unsigned long long got = atomicAdd(counter, lane_id() == 0 ? 1ULL : 0ULL);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(got));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(got >> 32));
+    return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
 // keep the k lowest set bits of mask (k <= 0: none, k >= popcount: all)
 __device__ __forceinline__ uint64_t lowest_bits(uint64_t mask, int k)
 {

@@ -251,17 +251,12 @@ __global__ __launch_bounds__(kWave) void uni_kernel(ConfigArrays cfg, int64_t n,
                                                     TimesOut times, SchedOut sched, char *slots, size_t slot_bytes,
                                                     unsigned long long *ticket)
 {
-    __shared__ unsigned long long s_next;
     const int lane = lane_id();
     UniState<T, kSched> st = carve_uni<T, kSched>(slots + static_cast<size_t>(blockIdx.x) * slot_bytes, p_max);
     for (;;) {
-        if (lane == 0) s_next = atomicAdd(ticket, 1ULL);
-        __syncthreads();
-        const int64_t i = static_cast<int64_t>(s_next);
-        __syncthreads();
+        const int64_t i = next_ticket(ticket);
         if (i >= n) break;
         Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
-        if (!kSched && lane == 0) write_closed_forms<T>(times, i, c, model);
         int32_t status = c.status;
         UniOut<T, kSched> out{sched.src, sched.dst, sched.seg, static_cast<T *>(sched.tstart), 0};
         if (kSched && status == PRS_CFG_OK) {
@@ -271,7 +266,8 @@ __global__ __launch_bounds__(kWave) void uni_kernel(ConfigArrays cfg, int64_t n,
         }
         T result = CostTraits<T>::bad();
         if (status == PRS_CFG_OK) result = run_uni<T, kSched>(c, st, out, &status);
-        if (lane == 0) {
+        if (lane == 0) {                  // the only lane-dependent branch of the loop body
+            if (!kSched) write_closed_forms<T>(times, i, c, model);
             T *tg = static_cast<T *>(kSched ? sched.T_greedy : times.greedy);
             int32_t *cs = kSched ? sched.cfg_status : times.cfg_status;
             if (tg) tg[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();
