@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of the whole path over the 100,000-configuration sweep
+(p in [2,1024], up to 512 segments, fp64 costs): completion times and baselines
+under both port models (simulate_completion_batch), the schedules themselves
+under both models (greedy_schedule_batch), and the replay of the p = 256,
+64-segment uni-greedy schedule over 256 buffers of 2^22 elements, once int32 and
+once fp32 (replay_reduction).  Inputs are resident in HBM before the timed
+region.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+N_CONFIGS = 100_000
+P_MAX, Q_MAX = 1024, 512
+REPLAY_P, REPLAY_Q, REPLAY_N = 256, 64, 1 << 22
+# published peaks of the chip: 256 CUs x 64 fp64 lanes x 2.4 GHz (one add or compare per lane and cycle;
+# the 78.6 TFLOP/s figure counts a fused multiply-add as two), HBM3E 8 TB/s
+PEAK_FP64_OPS = 256 * 64 * 2.4e9
+PEAK_HBM = 8.0e12
+# algorithmic operations per send/receive pair (the arithmetic the method itself needs):
+# Algorithm 1: two comparisons to pick the two smallest of two sorted fronts, t + tcomm, + tcomp
+OPS_PER_PAIR_UNI = 4
+# Algorithm 2: S <= t, R <= t and the two COMP comparisons for sender and receiver, t + tcomm, + tcomp
+OPS_PER_PAIR_BI = 10
+
+
+def cpu_baseline(host, seconds_hint=20.0):
+    """The oracle as it stands on this machine's cores, on a prefix of the same sweep."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+
+    oracle.build()
+    cores = min(16, os.cpu_count() or 1)
+    sample = 1024
+    idx = np.arange(sample)
+
+    def one(i):
+        oracle.simulate_batch(host, oracle.UNI, index=[i])
+        oracle.simulate_batch(host, oracle.BI, index=[i])
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(one, idx, chunksize=4))
+    dt = time.perf_counter() - t0
+    return {"value": 2 * sample / dt, "unit": "schedules/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample} configurations of the 100,000-configuration sweep, uni-greedy and bi-greedy "
+                      f"completion times with baselines, {dt:.1f} s of wall time"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the sweep is a batch of independent configurations and nothing here "
+              "spans devices; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1310_4645_amd as prs
+    import prs_inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    prs.load_library()
+
+    host = prs_inputs.uni_sweep(N_CONFIGS)
+    dev = prs.DeviceConfigs.from_host(host)
+    off = prs.prs_pair_offsets(dev, P_MAX, Q_MAX)
+    torch.cuda.synchronize()
+    n_pairs = int(off[-1].item())
+
+    # buffers allocated once, outside the timed region
+    f64, i32 = torch.float64, torch.int32
+    times = {m: {k: torch.empty(N_CONFIGS, dtype=f64, device="cuda")
+                 for k in ("greedy", "binomial", "pipeline", "binary", "revopt", "butterfly", "lower_bound")}
+             for m in (prs.PRS_UNI, prs.PRS_BI)}
+    for m in times:
+        times[m]["q_eff"] = torch.empty(N_CONFIGS, dtype=i32, device="cuda")
+        times[m]["cfg_status"] = torch.empty(N_CONFIGS, dtype=i32, device="cuda")
+    src = torch.empty(n_pairs, dtype=i32, device="cuda")
+    dst = torch.empty(n_pairs, dtype=i32, device="cuda")
+    seg = torch.empty(n_pairs, dtype=i32, device="cuda")
+    tst = torch.empty(n_pairs, dtype=f64, device="cuda")
+    ws = {}
+    for call in (prs.PRS_CALL_SIMULATE, prs.PRS_CALL_SCHEDULE):
+        for m in (prs.PRS_UNI, prs.PRS_BI):
+            nbytes = prs.prs_workspace_bytes(call, m, prs.PRS_COST_F64, N_CONFIGS, P_MAX, Q_MAX)
+            ws[(call, m)] = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+
+    # replay workload: the p = 256, 64-segment uni-greedy schedule and its 2 x 4 GiB of buffers
+    rcfg = prs.DeviceConfigs.from_host(prs_inputs.replay_config())
+    roff = prs.prs_pair_offsets(rcfg, REPLAY_P, REPLAY_Q)
+    rsch = prs.greedy_schedule_batch(rcfg, prs.PRS_UNI, REPLAY_P, REPLAY_Q, roff, (REPLAY_P - 1) * REPLAY_Q)
+    gen = torch.Generator(device="cuda").manual_seed(prs_inputs.SEED_REPLAY)
+    buf_i = torch.randint(-2 ** 20, 2 ** 20 + 1, (REPLAY_P, REPLAY_N), dtype=i32, device="cuda", generator=gen)
+    buf_f = torch.randn((REPLAY_P, REPLAY_N), dtype=torch.float32, device="cuda", generator=gen)
+    out_i = torch.empty(REPLAY_N, dtype=i32, device="cuda")
+    out_f = torch.empty(REPLAY_N, dtype=torch.float32, device="cuda")
+    seg_off = np.arange(REPLAY_Q + 1, dtype=np.int64) * (REPLAY_N // REPLAY_Q)
+    rws = torch.empty(prs.prs_workspace_bytes(prs.PRS_CALL_REPLAY, 0, 0, 1, REPLAY_P, REPLAY_Q) + 256,
+                      dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    names = ["simulate_uni", "simulate_bi", "schedule_uni", "schedule_bi", "replay_i32", "replay_f32"]
+
+    def step(events=None):
+        def mark(k):
+            if events is not None:
+                events[k].record()
+        mark(0)
+        prs.simulate_completion_batch(dev, prs.PRS_UNI, P_MAX, Q_MAX, out=times[prs.PRS_UNI],
+                                      workspace=ws[(prs.PRS_CALL_SIMULATE, prs.PRS_UNI)])
+        mark(1)
+        prs.simulate_completion_batch(dev, prs.PRS_BI, P_MAX, Q_MAX, out=times[prs.PRS_BI],
+                                      workspace=ws[(prs.PRS_CALL_SIMULATE, prs.PRS_BI)])
+        mark(2)
+        prs.greedy_schedule_batch(dev, prs.PRS_UNI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
+                                  workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI)])
+        mark(3)
+        prs.greedy_schedule_batch(dev, prs.PRS_BI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
+                                  workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_BI)])
+        mark(4)
+        prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_i, out=out_i, workspace=rws)
+        mark(5)
+        prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_f, out=out_f, workspace=rws)
+        mark(6)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    part_ms = {nm: float(np.mean([ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)]))
+               for k, nm in enumerate(names)}
+
+    # sanity of what was timed: all configurations valid, replay finished
+    assert int((times[prs.PRS_UNI]["cfg_status"] != 0).sum().item()) == 0
+    assert int((times[prs.PRS_BI]["cfg_status"] != 0).sum().item()) == 0
+
+    # roofline of the dominant kernel (the launch that takes the largest share of the step)
+    dominant = max(part_ms, key=part_ms.get)
+    if dominant.startswith("replay"):
+        alg = 4.0 * REPLAY_N * (REPLAY_P + 1)
+        roof = {"bound": "hbm", "achieved": alg / (part_ms[dominant] * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
+    else:
+        ops = n_pairs * (OPS_PER_PAIR_UNI if dominant.endswith("uni") else OPS_PER_PAIR_BI)
+        roof = {"bound": "alu", "achieved": ops / (part_ms[dominant] * 1e-3) / 1e12, "peak": PEAK_FP64_OPS / 1e12,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = dominant
+    replay_bytes = 4.0 * REPLAY_N * (REPLAY_P + 1)
+    out = {
+        "metric": "greedy schedules simulated/sec (uni+bi, p<=65536) + replay HBM GB/s vs peak",
+        "value": 2 * N_CONFIGS / (ms_per_step * 1e-3), "unit": "schedules/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "configs[1]+configs[2]: 100,000 seeded configurations, p in [2,1024], q_req in [1,512], "
+                               "fp64 costs, uni- and bi-greedy completion times, baselines and full schedules; "
+                               "plus configs[4]: replay of the p=256, q=64 uni-greedy schedule over 256 x 2^22 int32 and fp32",
+                   "n_configs": N_CONFIGS, "pairs_per_model": n_pairs},
+        "breakdown_ms": part_ms,
+        "pairs_per_s": {"uni_simulate": n_pairs / (part_ms["simulate_uni"] * 1e-3),
+                        "bi_simulate": n_pairs / (part_ms["simulate_bi"] * 1e-3),
+                        "uni_schedule": n_pairs / (part_ms["schedule_uni"] * 1e-3),
+                        "bi_schedule": n_pairs / (part_ms["schedule_bi"] * 1e-3)},
+        "replay": {"i32_GBps": replay_bytes / (part_ms["replay_i32"] * 1e-3) / 1e9,
+                   "f32_GBps": replay_bytes / (part_ms["replay_f32"] * 1e-3) / 1e9,
+                   "peak_GBps": PEAK_HBM / 1e9, "algorithmic_bytes": replay_bytes},
+        "schedule_emission_GBps": {"uni": n_pairs * 20.0 / (part_ms["schedule_uni"] * 1e-3) / 1e9,
+                                   "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
