@@ -84,6 +84,18 @@ template <typename T> __device__ __forceinline__ int count_less(const T *X, int 
     return lo - base;
 }
 
+// One lane sorts X/I[lo, hi) by (value, index); only entries with equal values are ever out of place.
+template <typename T> __device__ void insertion_sort(T *X, int32_t *I, int lo, int hi)
+{
+    for (int i = lo + 1; i < hi; ++i) {
+        const T x = X[i];
+        const int32_t id = I[i];
+        int j = i;
+        while (j > lo && key_less<T, true>(x, id, X[j - 1], I[j - 1])) { X[j] = X[j - 1]; I[j] = I[j - 1]; --j; }
+        X[j] = x; I[j] = id;
+    }
+}
+
 template <typename T, bool kSched> struct UniOut {
     int32_t *src, *dst, *seg;
     T *tstart;
@@ -189,7 +201,30 @@ __device__ T run_uni(const Config<T> &c, UniState<T, kSched> st, const UniOut<T,
                     int32_t s = g1, d = g2;
                     if (g1 == 0) { s = g2; d = 0; }           // the root never sends (Lemma 1 (ii))
                     const T tc = t + cc;
-                    st.Sx[ns + kp] = tc; st.Sid[ns + kp] = s;
+                    // Senders of one run of equal t leave with the same value and must enter S in index
+                    // order.  Inside a run they already are, except that the run's first pair may be
+                    // led by a processor left over from an earlier, smaller value: rank that one sender
+                    // among the others and shift those with smaller index down by one.
+                    int rs = 0;
+                    for (int len = kp; len > 0;) {             // first pair of this run
+                        const int half = len >> 1;
+                        if (st.Mx[2 * (rs + half) + 1] < t) { rs += half + 1; len -= half + 1; } else len = half;
+                    }
+                    int pos = kp;
+                    const int32_t f = st.Mid[2 * rs];
+                    if (st.Mx[2 * rs] < t && f != 0) {
+                        if (kp == rs) {
+                            int cnt = 0;
+                            for (int len = npairs - rs - 1; len > 0;) {
+                                const int half = len >> 1, j = rs + 1 + cnt + half;
+                                if (!(t < st.Mx[2 * j + 1]) && st.Mid[2 * j] < f) { cnt += half + 1; len -= half + 1; } else len = half;
+                            }
+                            pos = rs + cnt;
+                        } else if (s < f) {
+                            pos = kp - 1;
+                        }
+                    }
+                    st.Sx[ns + pos] = tc; st.Sid[ns + pos] = s;
                     st.Bx[jb + kp] = tc + gg; st.Bid[jb + kp] = d;
                     const int64_t o = out.base + static_cast<int64_t>(k) * (p - 1) + ns + kp;
                     if (out.src) out.src[o] = s;
@@ -198,28 +233,16 @@ __device__ T run_uni(const Config<T> &c, UniState<T, kSched> st, const UniOut<T,
                     if (out.tstart) out.tstart[o] = t;
                 }
                 __syncthreads();
-                // equal values from different t may arrive out of index order: detect, repair
+                // values produced at different t that round to the same double can still arrive out of
+                // index order: detect (B now, S at the end of the segment) and let one lane repair
                 bool bad = false;
                 const int live_b = ib + cntB;
                 for (int kp = lane; kp < npairs; kp += kWave) {
-                    const int si = ns + kp, bi = jb + kp;
-                    if (si > 0 && key_less<T, true>(st.Sx[si], st.Sid[si], st.Sx[si - 1], st.Sid[si - 1])) bad = true;
+                    const int bi = jb + kp;
                     if (bi > live_b && key_less<T, true>(st.Bx[bi], st.Bid[bi], st.Bx[bi - 1], st.Bid[bi - 1])) bad = true;
                 }
                 if (ballot64(bad) != 0) {
-                    if (lane == 0) {
-                        for (int pass = 0; pass < 2; ++pass) {
-                            T *X = pass ? st.Bx : st.Sx;
-                            int32_t *I = pass ? st.Bid : st.Sid;
-                            const int lo = pass ? live_b : 0, hi = pass ? jb + npairs : ns + npairs;
-                            for (int i = lo + 1; i < hi; ++i) {
-                                const T x = X[i]; const int32_t id = I[i];
-                                int j = i;
-                                while (j > lo && key_less<T, true>(x, id, X[j - 1], I[j - 1])) { X[j] = X[j - 1]; I[j] = I[j - 1]; --j; }
-                                X[j] = x; I[j] = id;
-                            }
-                        }
-                    }
+                    if (lane == 0) insertion_sort<T>(st.Bx, st.Bid, live_b, jb + npairs);
                     __syncthreads();
                 }
             }
@@ -231,6 +254,13 @@ __device__ T run_uni(const Config<T> &c, UniState<T, kSched> st, const UniOut<T,
         if (!kSched) {
             if (lane == 0) st.Sx[p - 1] = root_time;     // the root holds the maximum
         } else {
+            bool bad = false;
+            for (int i = lane + 1; i < p - 1; i += kWave)
+                if (key_less<T, true>(st.Sx[i], st.Sid[i], st.Sx[i - 1], st.Sid[i - 1])) bad = true;
+            if (ballot64(bad) != 0) {
+                if (lane == 0) insertion_sort<T>(st.Sx, st.Sid, 0, p - 1);
+                __syncthreads();
+            }
             // key (root_time, 0) goes before every equal value: shift that tail up by one
             const int pos = count_less(st.Sx, 0, p - 1, root_time);
             const int tail = (p - 1) - pos;
