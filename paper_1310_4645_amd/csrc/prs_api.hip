@@ -5,9 +5,8 @@
 
 namespace prs {
 
-constexpr size_t kHeaderBytes = 256;       // ticket counter at the start of the workspace
-constexpr int kMaxGrid = 4096;             // wavefront-sized blocks resident at once, at most
-constexpr size_t kMaxWorkspace = static_cast<size_t>(16) << 30;   // what prs_workspace_bytes asks for, at most (if 512 slots fit)
+constexpr size_t kHeaderBytes = 256;
+constexpr size_t kMaxWorkspace = static_cast<size_t>(16) << 30;   // slots of the global-memory class, at most (if 256 of them fit)
 
 __global__ void clear_words(unsigned long long *w, int count)
 {
@@ -64,28 +63,77 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
     return hipGetLastError();
 }
 
-static int grid_for(int64_t n, size_t slot, size_t workspace_bytes)
-{
-    int64_t g = n < kMaxGrid ? n : kMaxGrid;
-    if (g < 1) g = 1;
-    if (workspace_bytes > kHeaderBytes && slot > 0) {
-        const int64_t fit = static_cast<int64_t>((workspace_bytes - kHeaderBytes) / slot);
-        if (fit < g) g = fit;
-    } else {
-        g = 0;
-    }
-    return static_cast<int>(g);
-}
+// ---- size classes and workspace layout (shared by prs_workspace_bytes and the launches) --------------
+constexpr int32_t kClassP[kClasses - 1] = {64, 256, 1024};   // p limits of the LDS classes
+constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
+constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 
-static size_t slot_bytes_for(int call, int model, int32_t p_max, int32_t q_max)
+struct ClassSpec {
+    int32_t p_cap;            // capacity of the per-processor arrays of this class
+    bool lds;                 // state (uni) / small arrays and maybe the bitmap (bi) in LDS
+    size_t lds_bytes;
+    int32_t lds_bitmap_bytes;
+    size_t slot_bytes, slot_offset;
+    int grid;
+};
+
+struct Layout {
+    size_t header, order, total;
+    ClassSpec cls[kClasses];
+};
+
+static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t q_max)
 {
-    if (model == PRS_UNI) return uni_slot_bytes(call == PRS_CALL_SCHEDULE, p_max);
-    return bi_slot_bytes(p_max, q_max);
+    Layout L;
+    const bool sched = call == PRS_CALL_SCHEDULE;
+    L.header = 0;
+    L.order = plan_header_bytes();
+    size_t off = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
+    for (int k = 0; k < kClasses; ++k) {
+        ClassSpec &c = L.cls[k];
+        const bool last = k == kClasses - 1;
+        c.p_cap = last ? p_max : (kClassP[k] < p_max ? kClassP[k] : p_max);
+        c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0;
+        if (model == PRS_UNI) {
+            const size_t st = uni_state_bytes(sched, c.p_cap);
+            if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
+            else c.slot_bytes = st;
+        } else {
+            const size_t small = bi_small_bytes(c.p_cap, q_max), bitmap = bi_bitmap_bytes(c.p_cap, q_max);
+            if (!last && small <= kLdsPerBlockMax / 2) {
+                c.lds = true;
+                c.lds_bitmap_bytes = static_cast<int32_t>(bitmap < kBitmapLdsMax ? bitmap : kBitmapLdsMax);
+                c.lds_bytes = small + static_cast<size_t>(c.lds_bitmap_bytes);
+            }
+            c.slot_bytes = bi_slot_bytes(c.p_cap, q_max, c.lds);
+        }
+        int64_t g;
+        if (c.lds) {
+            int64_t per_cu = static_cast<int64_t>(kLdsPerCU / (c.lds_bytes < 1024 ? 1024 : c.lds_bytes));
+            if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
+            if (per_cu < 1) per_cu = 1;
+            g = per_cu * kCUs;
+        } else {
+            g = kGlobalClassGrid;
+            while (g > 256 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;   // big slots: fewer resident blocks
+        }
+        if (g > n) g = n < 1 ? 1 : n;
+        if (k > 0 && kClassP[k - 1] >= p_max) g = 0;      // p_max rules this class out
+        c.grid = static_cast<int>(g);
+        c.slot_offset = off;
+        off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
+    }
+    L.total = off;
+    return L;
 }
 
 static bool bad_common(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max)
 {
-    if (!cfg || n < 0 || (model != PRS_UNI && model != PRS_BI) || (cost != PRS_COST_I64 && cost != PRS_COST_F64)) return true;
+    if (!cfg || n < 0 || n >= (INT64_C(1) << 31) || (model != PRS_UNI && model != PRS_BI) ||
+        (cost != PRS_COST_I64 && cost != PRS_COST_F64))
+        return true;
     if (p_max < 2 || p_max > (1 << 20) || q_max < 1 || q_max > (1 << 20)) return true;
     if (n > 0 && (!cfg->p || !cfg->q_req || !cfg->m || !cfg->alpha || !cfg->beta || !cfg->gamma)) return true;
     return false;
@@ -96,22 +144,40 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
 {
     if (n == 0) return PRS_OK;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
-    const size_t slot = slot_bytes_for(call, model, p_max, q_max);
-    const int grid = grid_for(n, slot, workspace_bytes);
-    if (grid < 1) return PRS_ENOSPC;
-    UniLaunch L;
-    L.cfg = ConfigArrays{cfg->p, cfg->q_req, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
-    L.n = n; L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
-    L.want_schedule = call == PRS_CALL_SCHEDULE;
-    L.times = times; L.sched = sched;
-    L.slots = static_cast<char *>(workspace) + kHeaderBytes;
-    L.slot_bytes = slot;
-    L.ticket = static_cast<unsigned long long *>(workspace);
-    L.grid = grid;
-    L.stream = static_cast<hipStream_t>(stream);
-    if (launch_clear(L.ticket, 4, L.stream) != hipSuccess) return PRS_EDEVICE;
-    const hipError_t err = model == PRS_UNI ? launch_uni(L) : launch_bi(L);
-    return err == hipSuccess ? PRS_OK : PRS_EDEVICE;
+    const Layout lay = make_layout(call, model, n, p_max, q_max);
+    if (workspace_bytes < lay.total) return PRS_ENOSPC;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PlanLaunch P;
+    P.cfg = ConfigArrays{cfg->p, cfg->q_req, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
+    P.n = n; P.p_max = p_max; P.q_max = q_max; P.cost = cost;
+    for (int k = 0; k < kClasses - 1; ++k) P.limits.p[k] = kClassP[k];
+    P.header = reinterpret_cast<PlanHeader *>(ws + lay.header);
+    P.order = reinterpret_cast<int32_t *>(ws + lay.order);
+    P.stream = st;
+    if (launch_plan(P) != hipSuccess) return PRS_EDEVICE;
+    // heaviest class first; a class without configurations ends at once
+    for (int k = kClasses - 1; k >= 0; --k) {
+        const ClassSpec &c = lay.cls[k];
+        if (c.grid == 0) continue;                       // no configuration can fall in this class
+        UniLaunch L;
+        L.cfg = P.cfg;
+        L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
+        L.want_schedule = call == PRS_CALL_SCHEDULE;
+        L.times = times; L.sched = sched;
+        L.plan = P.header; L.order = P.order; L.cls = k;
+        L.lds_p = c.lds ? c.p_cap : 0;
+        L.lds_bitmap_bytes = c.lds_bitmap_bytes;
+        L.lds_bytes = c.lds_bytes;
+        L.slots = ws + c.slot_offset;
+        L.slot_bytes = c.slot_bytes;
+        L.slot_p = c.p_cap; L.slot_q = q_max;
+        L.grid = c.grid;
+        L.stream = st;
+        const hipError_t err = model == PRS_UNI ? launch_uni(L) : launch_bi(L);
+        if (err != hipSuccess) return PRS_EDEVICE;
+    }
+    return PRS_OK;
 }
 
 }  // namespace prs
@@ -129,10 +195,7 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
     if (call == PRS_CALL_REPLAY) return replay_workspace_bytes(p_max, q_max);
     if (call == PRS_CALL_OFFSETS) return kHeaderBytes;
     if (call != PRS_CALL_SIMULATE && call != PRS_CALL_SCHEDULE) return 0;
-    int64_t g = n < kMaxGrid ? (n < 1 ? 1 : n) : kMaxGrid;
-    const size_t slot = slot_bytes_for(call, model, p_max, q_max);
-    while (g > 512 && static_cast<size_t>(g) * slot > kMaxWorkspace) g /= 2;   // fewer resident configurations when each is big
-    return kHeaderBytes + static_cast<size_t>(g) * slot;
+    return make_layout(call, model, n, p_max, q_max).total;
 }
 
 int simulate_completion_batch(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,

@@ -27,53 +27,83 @@ namespace prs {
 
 __host__ __device__ inline size_t bi_align(size_t v) { return (v + 255) / 256 * 256; }
 
-struct BiLayout {
-    size_t S, R, C1, nsent, masks, pref, sendList, recvList, rem, sent, total;
+// Small arrays of a configuration: bit sets, list positions, pairing lists, per-segment counters.
+struct BiSmall {
+    size_t masks, pref, sendList, recvList, rem, total;
     int W;
 };
 
-__host__ __device__ inline BiLayout bi_layout(int32_t p_max, int32_t q_max)
+__host__ __device__ inline BiSmall bi_small_layout(int32_t p_cap, int32_t q_cap)
 {
-    BiLayout L;
-    const size_t p = static_cast<size_t>(p_max), q = static_cast<size_t>(q_max);
+    BiSmall L;
+    const size_t p = static_cast<size_t>(p_cap), q = static_cast<size_t>(q_cap);
     L.W = static_cast<int>((p + 63) / 64);
     size_t o = 0;
-    L.S = o; o += bi_align(p * 8);
-    L.R = o; o += bi_align(p * 8);
-    L.C1 = o; o += bi_align(p * 8);
-    L.nsent = o; o += bi_align(p * 4);
     L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 9);   // 9 word arrays
     L.pref = o; o += bi_align(static_cast<size_t>(L.W) * 4 * 2);
     L.sendList = o; o += bi_align((p / 2 + 1) * 4);
     L.recvList = o; o += bi_align((p / 2 + 1) * 4);
     L.rem = o; o += bi_align(q * 4);
-    L.sent = o; o += bi_align(static_cast<size_t>(L.W) * q * 8);
     L.total = o;
     return L;
 }
 
-size_t bi_slot_bytes(int32_t p_max, int32_t q_max) { return bi_layout(p_max, q_max).total; }
+// Per-processor times and counters: always in the block's workspace slot.
+struct BiBig { size_t S, R, C1, nsent, total; };
+
+__host__ __device__ inline BiBig bi_big_layout(int32_t p_cap)
+{
+    BiBig L;
+    const size_t p = static_cast<size_t>(p_cap);
+    size_t o = 0;
+    L.S = o; o += bi_align(p * 8);
+    L.R = o; o += bi_align(p * 8);
+    L.C1 = o; o += bi_align(p * 8);
+    L.nsent = o; o += bi_align(p * 4);
+    L.total = o;
+    return L;
+}
+
+size_t bi_small_bytes(int32_t p_cap, int32_t q_cap) { return bi_small_layout(p_cap, q_cap).total; }
+__host__ __device__ inline size_t bi_bitmap_size(int32_t p_cap, int32_t q_cap)
+{
+    return bi_align(static_cast<size_t>((p_cap + 63) / 64) * static_cast<size_t>(q_cap) * 8);
+}
+size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap) { return bi_bitmap_size(p_cap, q_cap); }
+size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds)
+{
+    return bi_big_layout(p_cap).total + bi_bitmap_size(p_cap, q_cap) + (small_in_lds ? 0 : bi_small_bytes(p_cap, q_cap));
+}
+
+struct BiState {
+    char *small;         // BiSmall arrays (LDS or slot)
+    char *big;           // BiBig arrays (slot)
+    uint64_t *sent;      // [q][W] bitmap (LDS if it fits, else slot)
+    int Wcap;            // words per mask array as laid out
+    BiSmall sl;
+    BiBig bl;
+};
 
 template <typename T, bool kSched>
-__device__ T run_bi(const Config<T> &c, char *slot, const BiLayout &lay, const SchedOut &sched, int64_t out_base,
-                    int32_t *status)
+__device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched, int64_t out_base, int32_t *status)
 {
     const int lane = lane_id();
     const int p = c.p, q = c.q;
-    const int W = (p + 63) >> 6;                        // words in use (<= lay.W)
-    T *S = reinterpret_cast<T *>(slot + lay.S);
-    T *R = reinterpret_cast<T *>(slot + lay.R);
-    T *C1 = reinterpret_cast<T *>(slot + lay.C1);
-    int32_t *nsent = reinterpret_cast<int32_t *>(slot + lay.nsent);
-    uint64_t *mk = reinterpret_cast<uint64_t *>(slot + lay.masks);
-    uint64_t *sfree = mk, *rfree = mk + lay.W, *compF = mk + 2 * lay.W, *compL = mk + 3 * lay.W;
-    uint64_t *soW = mk + 4 * lay.W, *roW = mk + 5 * lay.W, *frW = mk + 6 * lay.W;
-    uint64_t *sendSet = mk + 7 * lay.W, *recvSet = mk + 8 * lay.W;
-    int32_t *prefS = reinterpret_cast<int32_t *>(slot + lay.pref), *prefR = prefS + lay.W;
-    int32_t *sendList = reinterpret_cast<int32_t *>(slot + lay.sendList);
-    int32_t *recvList = reinterpret_cast<int32_t *>(slot + lay.recvList);
-    int32_t *rem = reinterpret_cast<int32_t *>(slot + lay.rem);
-    uint64_t *sent = reinterpret_cast<uint64_t *>(slot + lay.sent);      // [q][W]
+    const int W = (p + 63) >> 6;                        // words in use
+    T *S = reinterpret_cast<T *>(bs.big + bs.bl.S);
+    T *R = reinterpret_cast<T *>(bs.big + bs.bl.R);
+    T *C1 = reinterpret_cast<T *>(bs.big + bs.bl.C1);
+    int32_t *nsent = reinterpret_cast<int32_t *>(bs.big + bs.bl.nsent);
+    uint64_t *mk = reinterpret_cast<uint64_t *>(bs.small + bs.sl.masks);
+    const int Wc = bs.Wcap;
+    uint64_t *sfree = mk, *rfree = mk + Wc, *compF = mk + 2 * Wc, *compL = mk + 3 * Wc;
+    uint64_t *soW = mk + 4 * Wc, *roW = mk + 5 * Wc, *frW = mk + 6 * Wc;
+    uint64_t *sendSet = mk + 7 * Wc, *recvSet = mk + 8 * Wc;
+    int32_t *prefS = reinterpret_cast<int32_t *>(bs.small + bs.sl.pref), *prefR = prefS + Wc;
+    int32_t *sendList = reinterpret_cast<int32_t *>(bs.small + bs.sl.sendList);
+    int32_t *recvList = reinterpret_cast<int32_t *>(bs.small + bs.sl.recvList);
+    int32_t *rem = reinterpret_cast<int32_t *>(bs.small + bs.sl.rem);
+    uint64_t *sent = bs.sent;                           // [q][W]
 
     for (int i = lane; i < p; i += kWave) { S[i] = 0; R[i] = 0; C1[i] = 0; nsent[i] = 0; }
     for (int j = lane; j < q; j += kWave) rem[j] = p - 1;
@@ -222,17 +252,28 @@ __device__ T run_bi(const Config<T> &c, char *slot, const BiLayout &lay, const S
     return Tmax;
 }
 
-template <typename T, bool kSched>
-__global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, int model,
-                                                   TimesOut times, SchedOut sched, char *slots, size_t slot_bytes,
-                                                   unsigned long long *ticket)
+template <typename T, bool kSched, bool kLds>
+__global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model, TimesOut times,
+                                                   SchedOut sched, PlanHeader *plan, const int32_t *order, int cls,
+                                                   int32_t state_p, int32_t state_q, int32_t lds_bitmap_bytes, char *slots,
+                                                   size_t slot_bytes)
 {
+    PRS_DYNAMIC_LDS(lds_raw);
     const int lane = lane_id();
-    const BiLayout lay = bi_layout(p_max, q_max);
     char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
+    BiState bs;
+    bs.sl = bi_small_layout(state_p, state_q);
+    bs.bl = bi_big_layout(state_p);
+    bs.Wcap = bs.sl.W;
+    bs.big = slot;
+    uint64_t *slot_bitmap = reinterpret_cast<uint64_t *>(slot + bs.bl.total);
+    bs.small = kLds ? lds_raw : slot + bs.bl.total + bi_bitmap_size(state_p, state_q);
+    uint64_t *lds_bitmap = reinterpret_cast<uint64_t *>(lds_raw + bs.sl.total);
+    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
     for (;;) {
-        const int64_t i = next_ticket(ticket);
-        if (i >= n) break;
+        const int64_t ticket = next_ticket(&plan->ticket[cls]);
+        if (ticket >= count) break;
+        const int64_t i = order[begin + ticket];
         Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
         int32_t status = c.status;
         int64_t base = 0;
@@ -242,7 +283,11 @@ __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, 
             if (base < 0 || base + cnt > sched.pair_capacity) status = PRS_CFG_TOO_LARGE;
         }
         T result = CostTraits<T>::bad();
-        if (status == PRS_CFG_OK) result = run_bi<T, kSched>(c, slot, lay, sched, base, &status);
+        if (status == PRS_CFG_OK) {
+            const int64_t bitmap_bytes = static_cast<int64_t>((c.p + 63) >> 6) * c.q * 8;
+            bs.sent = (kLds && bitmap_bytes <= lds_bitmap_bytes) ? lds_bitmap : slot_bitmap;
+            result = run_bi<T, kSched>(c, bs, sched, base, &status);
+        }
         __syncthreads();
         if (lane == 0) {                  // the only lane-dependent branch of the loop body
             if (!kSched) write_closed_forms<T>(times, i, c, model);
@@ -251,14 +296,20 @@ __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int64_t n, 
             if (tg) tg[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();
             if (cs) cs[i] = status;
         }
+        __syncthreads();
     }
 }
 
 template <typename T, bool kSched>
 static hipError_t launch_bi_t(const BiLaunch &L)
 {
-    hipLaunchKernelGGL((bi_kernel<T, kSched>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.model,
-                       L.times, L.sched, L.slots, L.slot_bytes, L.ticket);
+    if (L.lds_p > 0)
+        hipLaunchKernelGGL((bi_kernel<T, kSched, true>), dim3(L.grid), dim3(kWave), L.lds_bytes, L.stream, L.cfg, L.p_max, L.q_max,
+                           L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slot_q, L.lds_bitmap_bytes, L.slots,
+                           L.slot_bytes);
+    else
+        hipLaunchKernelGGL((bi_kernel<T, kSched, false>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.p_max, L.q_max,
+                           L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slot_q, 0, L.slots, L.slot_bytes);
     return hipGetLastError();
 }
 

@@ -11,6 +11,11 @@ namespace prs {
 
 constexpr int kWave = 64;
 
+// The dynamically sized LDS allocation of a kernel (one per kernel body).
+#ifndef PRS_DYNAMIC_LDS
+#define PRS_DYNAMIC_LDS(name) extern __shared__ __align__(256) char name[]
+#endif
+
 // ---------------------------------------------------------------- cost types
 template <typename T> struct CostTraits;
 template <> struct CostTraits<int64_t> {

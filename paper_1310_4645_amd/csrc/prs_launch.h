@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "prs_device.h"
+#include "prs_plan.h"
 
 namespace prs {
 
@@ -18,25 +19,35 @@ struct SchedOut {
     int32_t *cfg_status;
 };
 
+// One launch = one size class of the plan.  lds_p > 0: per-configuration state lives in LDS arrays sized
+// for lds_p processors (uni) / the small arrays and, if it fits lds_bitmap_bytes, the sent bitmap (bi);
+// slots then hold only what stays in global memory.  slot_p/slot_q size the slot arrays.
 struct UniLaunch {
     ConfigArrays cfg;
-    int64_t n;
     int32_t p_max, q_max;
     int model, cost;
     bool want_schedule;
     TimesOut times;
     SchedOut sched;
+    PlanHeader *plan;
+    const int32_t *order;
+    int cls;
+    int32_t lds_p;
+    int32_t lds_bitmap_bytes;
+    size_t lds_bytes;
     char *slots;
     size_t slot_bytes;
-    unsigned long long *ticket;
+    int32_t slot_p, slot_q;
     int grid;
     hipStream_t stream;
 };
 
 typedef UniLaunch BiLaunch;   // same fields; slots sized by bi_slot_bytes
 
-size_t uni_slot_bytes(bool sched, int32_t p_max);
-size_t bi_slot_bytes(int32_t p_max, int32_t q_max);
+size_t uni_state_bytes(bool sched, int32_t p_cap);                 // all of uni-greedy's state for p_cap processors
+size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lists, per-segment counters
+size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
+size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
 hipError_t launch_uni(const UniLaunch &L);
 hipError_t launch_bi(const BiLaunch &L);
 

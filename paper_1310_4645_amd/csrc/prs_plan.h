@@ -1,0 +1,39 @@
+// Work plan of a batch: configurations grouped into size classes (so that each class can keep its state
+// in an LDS allocation of matching size) and, inside a class, ordered from most to least work, so the
+// longest-running configurations start first.  Built on the device by three small kernels; no host sync.
+#pragma once
+
+#include "prs_device.h"
+
+namespace prs {
+
+constexpr int kClasses = 4;          // three LDS classes by p, one class with state in global memory
+constexpr int kWorkBuckets = 40;     // floor(log2(work)) buckets, heaviest first
+
+struct PlanHeader {
+    unsigned long long ticket[kClasses];
+    int32_t class_begin[kClasses];
+    int32_t class_count[kClasses];
+    int32_t hist[kClasses * kWorkBuckets];
+    int32_t start[kClasses * kWorkBuckets];
+    int32_t cursor[kClasses * kWorkBuckets];
+};
+
+struct ClassLimits { int32_t p[kClasses - 1]; };     // class k holds p <= limits.p[k]; the last class the rest
+
+struct PlanLaunch {
+    ConfigArrays cfg;
+    int64_t n;
+    int32_t p_max, q_max;
+    int cost;
+    ClassLimits limits;
+    PlanHeader *header;
+    int32_t *order;
+    hipStream_t stream;
+};
+
+hipError_t launch_plan(const PlanLaunch &L);
+
+__host__ __device__ inline size_t plan_header_bytes() { return (sizeof(PlanHeader) + 255) / 256 * 256; }
+
+}  // namespace prs

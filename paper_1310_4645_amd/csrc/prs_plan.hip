@@ -1,0 +1,75 @@
+#include "prs_plan.h"
+
+namespace prs {
+
+template <typename T>
+__device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, int32_t p_max, int32_t q_max,
+                                           const ClassLimits &lim)
+{
+    const Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
+    if (c.status != PRS_CFG_OK) return kWorkBuckets - 1;                 // nothing to do: lightest bucket of class 0
+    int cls = kClasses - 1;
+    for (int k = kClasses - 2; k >= 0; --k)
+        if (c.p <= lim.p[k]) cls = k;
+    const int64_t work = static_cast<int64_t>(c.p - 1) * c.q;
+    int lg = 63 - __builtin_clzll(static_cast<unsigned long long>(work) | 1ULL);
+    if (lg > kWorkBuckets - 1) lg = kWorkBuckets - 1;
+    return cls * kWorkBuckets + (kWorkBuckets - 1 - lg);
+}
+
+__global__ void plan_clear(PlanHeader *h)
+{
+    const int i = threadIdx.x;
+    if (i < kClasses) { h->ticket[i] = 0ULL; h->class_begin[i] = 0; h->class_count[i] = 0; }
+    for (int k = i; k < kClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
+}
+
+template <typename T>
+__global__ void plan_hist(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim, PlanHeader *h)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) atomicAdd(&h->hist[plan_bucket<T>(cfg, i, p_max, q_max, lim)], 1);
+}
+
+__global__ void plan_scan(PlanHeader *h)
+{
+    if (threadIdx.x != 0) return;
+    int32_t run = 0;
+    for (int c = 0; c < kClasses; ++c) {
+        h->class_begin[c] = run;
+        for (int b = 0; b < kWorkBuckets; ++b) {
+            h->start[c * kWorkBuckets + b] = run;
+            run += h->hist[c * kWorkBuckets + b];
+        }
+        h->class_count[c] = run - h->class_begin[c];
+    }
+}
+
+template <typename T>
+__global__ void plan_scatter(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim, PlanHeader *h,
+                             int32_t *order)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int b = plan_bucket<T>(cfg, i, p_max, q_max, lim);
+    const int32_t pos = h->start[b] + atomicAdd(&h->cursor[b], 1);
+    order[pos] = static_cast<int32_t>(i);
+}
+
+hipError_t launch_plan(const PlanLaunch &L)
+{
+    const unsigned blocks = static_cast<unsigned>((L.n + 255) / 256);
+    hipLaunchKernelGGL(plan_clear, dim3(1), dim3(256), 0, L.stream, L.header);
+    if (L.cost == PRS_COST_I64) {
+        hipLaunchKernelGGL((plan_hist<int64_t>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
+        hipLaunchKernelGGL((plan_scatter<int64_t>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
+    } else {
+        hipLaunchKernelGGL((plan_hist<double>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
+        hipLaunchKernelGGL((plan_scatter<double>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace prs

@@ -30,7 +30,7 @@ template <typename T, bool kSched> struct UniState {
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-size_t uni_slot_bytes(bool sched, int32_t p_max)
+size_t uni_state_bytes(bool sched, int32_t p_max)
 {
     const size_t tb = align_up(static_cast<size_t>(p_max) * 8, 256), ib = align_up(static_cast<size_t>(p_max) * 4, 256);
     return sched ? 4 * tb + 4 * ib : 3 * tb;
@@ -276,16 +276,21 @@ __device__ T run_uni(const Config<T> &c, UniState<T, kSched> st, const UniOut<T,
     return root_time;
 }
 
-template <typename T, bool kSched>
-__global__ __launch_bounds__(kWave) void uni_kernel(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, int model,
-                                                    TimesOut times, SchedOut sched, char *slots, size_t slot_bytes,
-                                                    unsigned long long *ticket)
+template <typename T, bool kSched, bool kLds>
+__global__ __launch_bounds__(kWave) void uni_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model, TimesOut times,
+                                                    SchedOut sched, PlanHeader *plan, const int32_t *order, int cls,
+                                                    int32_t state_p, char *slots, size_t slot_bytes)
 {
+    PRS_DYNAMIC_LDS(lds_raw);
     const int lane = lane_id();
-    UniState<T, kSched> st = carve_uni<T, kSched>(slots + static_cast<size_t>(blockIdx.x) * slot_bytes, p_max);
+    // all per-configuration state in LDS (classes with p <= state_p) or in this block's workspace slot
+    char *base = kLds ? lds_raw : slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
+    UniState<T, kSched> st = carve_uni<T, kSched>(base, state_p);
+    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
     for (;;) {
-        const int64_t i = next_ticket(ticket);
-        if (i >= n) break;
+        const int64_t ticket = next_ticket(&plan->ticket[cls]);
+        if (ticket >= count) break;
+        const int64_t i = order[begin + ticket];
         Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
         int32_t status = c.status;
         UniOut<T, kSched> out{sched.src, sched.dst, sched.seg, static_cast<T *>(sched.tstart), 0};
@@ -303,14 +308,19 @@ __global__ __launch_bounds__(kWave) void uni_kernel(ConfigArrays cfg, int64_t n,
             if (tg) tg[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();
             if (cs) cs[i] = status;
         }
+        __syncthreads();                  // the next configuration reuses the state arrays
     }
 }
 
 template <typename T, bool kSched>
 static hipError_t launch_uni_t(const UniLaunch &L)
 {
-    hipLaunchKernelGGL((uni_kernel<T, kSched>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.model,
-                       L.times, L.sched, L.slots, L.slot_bytes, L.ticket);
+    if (L.lds_p > 0)
+        hipLaunchKernelGGL((uni_kernel<T, kSched, true>), dim3(L.grid), dim3(kWave), L.lds_bytes, L.stream, L.cfg, L.p_max, L.q_max,
+                           L.model, L.times, L.sched, L.plan, L.order, L.cls, L.lds_p, L.slots, L.slot_bytes);
+    else
+        hipLaunchKernelGGL((uni_kernel<T, kSched, false>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.p_max, L.q_max,
+                           L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slots, L.slot_bytes);
     return hipGetLastError();
 }
 
