@@ -68,7 +68,12 @@ constexpr int32_t kClassP[kClasses - 1] = {64, 256, 1024};   // p limits of the 
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 
+constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
+constexpr int kGroupLpc[kClasses - 1] = {1, 4, 16};
+
 struct ClassSpec {
+    int lpc;                  // > 0: bi-greedy, several configurations per wavefront, lpc lanes each
+    size_t rows_per_group;    // words of sent-bit rows per configuration slot
     int32_t p_cap;            // capacity of the per-processor arrays of this class
     bool lds;                 // state (uni) / small arrays and maybe the bitmap (bi) in LDS
     size_t lds_bytes;
@@ -78,7 +83,7 @@ struct ClassSpec {
 };
 
 struct Layout {
-    size_t header, order, total;
+    size_t header, order, retry, total;
     ClassSpec cls[kClasses];
 };
 
@@ -90,19 +95,29 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     const bool sched = call == PRS_CALL_SCHEDULE;
     L.header = 0;
     L.order = plan_header_bytes();
-    size_t off = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
+    L.retry = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
+    size_t off = L.retry + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     for (int k = 0; k < kClasses; ++k) {
         ClassSpec &c = L.cls[k];
         const bool last = k == kClasses - 1;
         c.p_cap = last ? p_max : (kClassP[k] < p_max ? kClassP[k] : p_max);
-        c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0;
-        if (model == PRS_UNI) {
+        c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
+        if (model == PRS_BI && !last) {
+            // several configurations per wavefront; the slot of a wavefront holds the sent-bit rows of its groups
+            c.lpc = kGroupLpc[k];
+            c.lds = true;
+            c.lds_bytes = bi_group_lds_bytes(c.lpc);
+            const int32_t q_cap = q_max < kGroupQMax ? q_max : kGroupQMax;
+            c.rows_per_group = static_cast<size_t>(q_cap) * c.lpc;
+            c.slot_bytes = c.rows_per_group * 8 * (64 / c.lpc);
+        } else if (model == PRS_UNI) {
             const size_t st = uni_state_bytes(sched, c.p_cap);
             if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
             else c.slot_bytes = st;
         } else {
+            // general one-configuration-per-wavefront kernel: big p or many segments, and reruns
             const size_t small = bi_small_bytes(c.p_cap, q_max), bitmap = bi_bitmap_bytes(c.p_cap, q_max);
-            if (!last && small <= kLdsPerBlockMax / 2) {
+            if (small <= kLdsPerBlockMax / 2) {
                 c.lds = true;
                 c.lds_bitmap_bytes = static_cast<int32_t>(bitmap < kBitmapLdsMax ? bitmap : kBitmapLdsMax);
                 c.lds_bytes = small + static_cast<size_t>(c.lds_bitmap_bytes);
@@ -120,7 +135,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
             while (g > 256 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;   // big slots: fewer resident blocks
         }
         if (g > n) g = n < 1 ? 1 : n;
-        if (k > 0 && kClassP[k - 1] >= p_max) g = 0;      // p_max rules this class out
+        if (k > 0 && kClassP[k - 1] >= p_max && !(model == PRS_BI && last)) g = 0;      // p_max rules this class out
         c.grid = static_cast<int>(g);
         c.slot_offset = off;
         off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
@@ -152,14 +167,28 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
     P.cfg = ConfigArrays{cfg->p, cfg->q_req, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
     P.n = n; P.p_max = p_max; P.q_max = q_max; P.cost = cost;
     for (int k = 0; k < kClasses - 1; ++k) P.limits.p[k] = kClassP[k];
+    P.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
     P.header = reinterpret_cast<PlanHeader *>(ws + lay.header);
     P.order = reinterpret_cast<int32_t *>(ws + lay.order);
     P.stream = st;
     if (launch_plan(P) != hipSuccess) return PRS_EDEVICE;
+    int32_t *retry = reinterpret_cast<int32_t *>(ws + lay.retry);
     // heaviest class first; a class without configurations ends at once
     for (int k = kClasses - 1; k >= 0; --k) {
         const ClassSpec &c = lay.cls[k];
         if (c.grid == 0) continue;                       // no configuration can fall in this class
+        if (c.lpc > 0) {
+            BiGroupLaunch G;
+            G.cfg = P.cfg; G.p_max = p_max; G.q_max = q_max; G.model = model; G.cost = cost;
+            G.want_schedule = call == PRS_CALL_SCHEDULE;
+            G.times = times; G.sched = sched; G.plan = P.header; G.order = P.order; G.cls = k; G.lpc = c.lpc;
+            G.retry = retry;
+            G.rows = reinterpret_cast<uint64_t *>(ws + c.slot_offset);
+            G.rows_per_group = c.rows_per_group;
+            G.grid = c.grid; G.stream = st;
+            if (launch_bi_group(G) != hipSuccess) return PRS_EDEVICE;
+            continue;
+        }
         UniLaunch L;
         L.cfg = P.cfg;
         L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
@@ -176,6 +205,25 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         L.stream = st;
         const hipError_t err = model == PRS_UNI ? launch_uni(L) : launch_bi(L);
         if (err != hipSuccess) return PRS_EDEVICE;
+    }
+    if (model == PRS_BI) {
+        // configurations whose list of running groups did not fit go through the general kernel
+        const ClassSpec &c = lay.cls[kClasses - 1];
+        UniLaunch L;
+        L.cfg = P.cfg;
+        L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
+        L.want_schedule = call == PRS_CALL_SCHEDULE;
+        L.times = times; L.sched = sched;
+        L.plan = P.header; L.order = retry; L.cls = kRetryClass;
+        L.lds_p = c.lds ? c.p_cap : 0;
+        L.lds_bitmap_bytes = c.lds_bitmap_bytes;
+        L.lds_bytes = c.lds_bytes;
+        L.slots = ws + c.slot_offset;
+        L.slot_bytes = c.slot_bytes;
+        L.slot_p = c.p_cap; L.slot_q = q_max;
+        L.grid = c.grid;
+        L.stream = st;
+        if (launch_bi(L) != hipSuccess) return PRS_EDEVICE;
     }
     return PRS_OK;
 }

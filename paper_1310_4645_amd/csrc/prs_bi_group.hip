@@ -1,0 +1,325 @@
+// Bi-greedy schedules (Lowery & Langou, Algorithm 2, Section 6.2) for p <= 1024 on gfx950:
+// several configurations per wavefront.
+//
+// A configuration is run by LPC adjacent lanes (1, 4 or 16), lane w of the group owning processors
+// 64w .. 64w+63 as one machine word; a wavefront carries 64/LPC configurations at once.  Nothing is kept
+// per processor:
+//  - every send/receive pair scheduled in one visit (time t, segment j) has the same end of send
+//    t + tcomm(j) and the same end of combine, so the ports and computations of Algorithm 2 (S, R, C)
+//    are a short list of groups (end of send, end of combine, set of senders, set of receivers);
+//    a processor's send port is free iff it is in no group whose send still runs, and so on;
+//  - the number of segments a processor has sent (needed to drop finished processors from the
+//    candidate sets) is a bit-sliced counter: bit b of all 64 counts in one word;
+//  - M(i,j) "i has sent j" is one bit-set row per segment in the workspace;
+//  - pairing e-th sender with e-th receiver needs no lists: each sender writes its pair record at
+//    its rank among the senders, each receiver its own index at its rank among the receivers.
+// The visit itself is the same sequence of set operations as in the one-configuration kernel.
+// All lanes run one flat loop in which a group either visits the next segment or advances time, so
+// groups at different times and segments share the same instructions.
+#include "prs_device.h"
+#include "prs_launch.h"
+
+namespace prs {
+
+constexpr int kPlanes = 10;            // bit planes of the sent-segments counter: q <= 1023
+
+// Entries of the list of running groups per configuration.  A configuration that needs more is handed
+// to the one-configuration kernel.  PRS_BI_GROUP_CAP shrinks the list in test builds to force that path.
+#ifdef PRS_BI_GROUP_CAP
+__host__ __device__ constexpr int bi_group_capacity(int) { return PRS_BI_GROUP_CAP; }
+#else
+__host__ __device__ constexpr int bi_group_capacity(int lpc) { return lpc == 1 ? 16 : (lpc == 4 ? 22 : 28); }
+#endif
+
+// LDS per wavefront: `cap` list entries, each with the two set words of every lane and the two times of
+// every configuration in the wavefront
+// (the times twice when lanes share them: see the kernel)
+size_t bi_group_lds_bytes(int lpc)
+{
+    return static_cast<size_t>(bi_group_capacity(lpc)) * (64 * 16 + (64 / lpc) * 16 * (lpc == 1 ? 1 : 2));
+}
+
+template <int LPC> __device__ __forceinline__ int group_sum(int v)
+{
+#pragma unroll
+    for (int o = LPC / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, LPC);
+    return v;
+}
+
+// exclusive prefix sum over the LPC lanes of a group
+template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, int gl)
+{
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < LPC; o <<= 1) {
+        const int u = __shfl_up(inc, o, LPC);
+        if (gl >= o) inc += u;
+    }
+    return inc - v;
+}
+
+template <typename T, bool kSched, int LPC>
+__global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
+                                                         TimesOut times, SchedOut sched, PlanHeader *plan,
+                                                         const int32_t *order, int cls, int32_t *retry,
+                                                         uint64_t *rows, size_t rows_per_group)
+{
+    PRS_DYNAMIC_LDS(lds_raw);
+    constexpr int kCap = bi_group_capacity(LPC);
+    const int lane = lane_id();
+    const int gl = lane & (LPC - 1);                    // lane within the group = word index
+    const int group = (static_cast<int>(blockIdx.x) * kWave + lane) / LPC;
+    // group list in LDS, entry-major so that the 64 lanes of an entry touch consecutive addresses
+    constexpr int kGroups = kWave / LPC;
+    const int gw = lane / LPC;                                      // configuration slot within the wavefront
+    uint64_t *gSm = reinterpret_cast<uint64_t *>(lds_raw);          // [kCap][64] senders (this lane's word)
+    uint64_t *gRm = gSm + kCap * kWave;                             // [kCap][64] receivers
+    // The times of an entry are shared by the lanes of a configuration.  Dropping finished entries copies
+    // the list into a second buffer instead of compacting in place, so a lane never reads a slot that
+    // another lane of its group has already rewritten, whatever the order in which lanes get there.
+    constexpr int kBufs = LPC == 1 ? 1 : 2;
+    T *gS = reinterpret_cast<T *>(gRm + kCap * kWave);              // [kBufs][kCap][kGroups] end of send
+    T *gR = gS + kBufs * kCap * kGroups;                            // [kBufs][kCap][kGroups] end of combine
+    int cur = 0;                                                    // buffer in use
+    uint64_t *myrows = rows + static_cast<size_t>(group) * rows_per_group;   // [q][LPC] sent bits of this group
+    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    const T kInf = CostTraits<T>::inf();
+
+    // ---- per-group state (identical in all lanes of a group unless noted)
+    bool have = false;          // a configuration is loaded
+    bool exhausted = false;     // no more tickets
+    int64_t ci = 0;             // configuration index
+    Config<T> c;
+    int W = 0;
+    T t = 0, Tmax = 0, minNew = kInf;
+    int ndone = 0, segStart = 0, j = 0, jhi = -1, ng = 0, status = 0;
+    bool need_event = true, overflow = false;
+    int64_t emitted = 0, out_base = 0, events = 0;
+    uint64_t valid = 0, sfree = 0, rfree = 0, compF = 0, compL = 0;   // this lane's word
+    uint64_t cnt[kPlanes];
+#pragma unroll
+    for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
+    int cs = 0, cr = 0;
+    c.p = 2; c.q = 1; c.status = 0; c.c_full = c.c_last = c.g_full = c.g_last = 0;
+
+    for (;;) {
+        // ---------------------------------------------------------------- fetch a configuration
+        if (!have && !exhausted) {
+            unsigned long long got = atomicAdd(&plan->ticket[cls], gl == 0 ? 1ULL : 0ULL);
+            const uint32_t lo = __shfl(static_cast<uint32_t>(got), 0, LPC), hi = __shfl(static_cast<uint32_t>(got >> 32), 0, LPC);
+            const int64_t ticket = static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+            if (ticket >= count) {
+                exhausted = true;
+            } else {
+                ci = order[begin + ticket];
+                c = decode_config<T>(cfg, ci, p_max, q_max);
+                status = c.status;
+                out_base = 0;
+                if (kSched && status == PRS_CFG_OK) {
+                    out_base = sched.pair_offset[ci];
+                    const int64_t n_pairs = static_cast<int64_t>(c.p - 1) * c.q;
+                    if (out_base < 0 || out_base + n_pairs > sched.pair_capacity) status = PRS_CFG_TOO_LARGE;
+                }
+                have = true;
+                W = (c.p + 63) >> 6;
+                valid = 0;
+                if (gl < W) valid = (gl == W - 1 && (c.p & 63)) ? (UINT64_C(1) << (c.p & 63)) - 1 : ~UINT64_C(0);
+                t = 0; Tmax = 0; minNew = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
+                need_event = true; overflow = false; emitted = 0; events = 0;
+#pragma unroll
+                for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
+            }
+        }
+        // wavefront-wide exit: every group out of tickets and idle
+        if (ballot64(have) == 0 && ballot64(!exhausted) == 0) break;
+
+        // ---------------------------------------------------------------- finish a configuration
+        const bool finished = have && (status != PRS_CFG_OK || ndone == c.q || overflow);
+        if (finished) {
+            if (gl == 0) {
+                if (overflow) {
+                    retry[atomicAdd(&plan->class_count[kRetryClass], 1)] = static_cast<int32_t>(ci);   // rerun by the one-configuration kernel
+                } else {
+                    if (!kSched) write_closed_forms<T>(times, ci, c, model);
+                    T *tg = static_cast<T *>(kSched ? sched.T_greedy : times.greedy);
+                    int32_t *st = kSched ? sched.cfg_status : times.cfg_status;
+                    if (tg) tg[ci] = status == PRS_CFG_OK ? Tmax : CostTraits<T>::bad();
+                    if (st) st[ci] = status;
+                }
+            }
+            have = false;
+        }
+        const bool run = have && !finished;
+
+        // ---------------------------------------------------------------- advance time (Algorithm 2: t <- next port release)
+        if (run && need_event) {
+            T tn = t;
+            if (events > 0) {
+                tn = minNew;
+                for (int s = 0; s < ng; ++s) {
+                    const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
+                    if (se > t && se < tn) tn = se;
+                    if (re > t && re < tn) tn = re;
+                }
+                if (!(tn < kInf)) status = PRS_CFG_STALLED;
+            }
+            if (++events > 4 * static_cast<int64_t>(c.p) * c.q + 16) status = PRS_CFG_STALLED;
+            t = tn;
+            minNew = kInf;
+            // rebuild the port and computation sets from the groups still running; drop finished groups
+            uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0;
+            int keep = 0;
+            const int nxt = kBufs == 1 ? 0 : cur ^ 1;
+            for (int s = 0; s < ng; ++s) {
+                const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
+                const uint64_t sm = gSm[s * kWave + lane], rm = gRm[s * kWave + lane];
+                if (re > t || se > t) {
+                    if (se > t) sbusy |= sm;
+                    if (re > t) rbusy |= rm;
+                    const bool busy = se <= t && t < re;                  // receivers are computing
+                    const bool pend = t < se;                             // their computation starts at se
+                    if (busy || (pend && t + c.c_full > se)) cF |= rm;
+                    if (busy || (pend && t + c.c_last > se)) cL |= rm;
+                    gS[(nxt * kCap + keep) * kGroups + gw] = se;          // same value from every lane of the group
+                    gR[(nxt * kCap + keep) * kGroups + gw] = re;
+                    if (keep != s) { gSm[keep * kWave + lane] = sm; gRm[keep * kWave + lane] = rm; }
+                    ++keep;
+                }
+            }
+            ng = keep;
+            cur = nxt;
+            // processors that have sent all q segments take part in nothing any more
+            uint64_t fin = ~UINT64_C(0);
+#pragma unroll
+            for (int b = 0; b < kPlanes; ++b) fin &= ((c.q >> b) & 1) ? cnt[b] : ~cnt[b];
+            const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
+            const uint64_t live = valid & (~fin | rootbit);
+            sfree = live & ~rootbit & ~sbusy;                             // the root never sends
+            rfree = live & ~rbusy;
+            compF = cF; compL = cL;
+            cs = group_sum<LPC>(__popcll(sfree & ~compL));
+            cr = group_sum<LPC>(__popcll(rfree & ~compL));
+            j = segStart;
+            need_event = false;
+        }
+
+        // ---------------------------------------------------------------- one visit (t, j)
+        const bool visit = run && !need_event && status == PRS_CFG_OK;
+        if (visit) {
+            if (j >= c.q || cs == 0 || cr == 0) {
+                need_event = true;                                        // nothing more can pair at this t
+            } else {
+                const bool last = j == c.q - 1;
+                uint64_t row = 0;
+                if (j <= jhi && gl < W) row = myrows[static_cast<size_t>(j) * LPC + gl];
+                const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
+                const uint64_t memb = ~row & valid;                       // still hold segment j (root: until done)
+                int remj = group_sum<LPC>(__popcll(memb & ~rootbit));
+                if (remj == 0) {                                          // everybody has sent segment j
+                    if (j == segStart) ++segStart;
+                    ++j;
+                } else {
+                    const uint64_t comp = last ? compL : compF;
+                    const uint64_t sOK = memb & ~comp & sfree, rOK = memb & ~comp & rfree;
+                    const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
+                    const int pf = __popcll(fr);
+                    const int ns_ = group_sum<LPC>(__popcll(so)), nr_ = group_sum<LPC>(__popcll(ro)), nf_ = group_sum<LPC>(pf);
+                    int toSendLast, toRecvFirst;                          // free processors go to the shorter list
+                    if (ns_ == nr_) {
+                        toSendLast = toRecvFirst = nf_ / 2;
+                    } else if (ns_ < nr_) {
+                        const int y = nr_ - ns_, mm = nf_ < y ? nf_ : y, xx = (nf_ - mm) / 2;
+                        toSendLast = mm + xx; toRecvFirst = xx;
+                    } else {
+                        const int y = ns_ - nr_, mm = nf_ < y ? nf_ : y, xx = (nf_ - mm) / 2;
+                        toRecvFirst = mm + xx; toSendLast = xx;
+                    }
+                    const int sN = ns_ + toSendLast, rN = nr_ + toRecvFirst;
+                    const int l = sN < rN ? sN : rN;
+                    if (l > 0) {
+                        const int exF = group_exclusive_scan<LPC>(pf, gl);
+                        const uint64_t frR = lowest_bits(fr, toRecvFirst - exF);
+                        const uint64_t frS = highest_bits(fr, exF + pf - (nf_ - toSendLast));
+                        uint64_t sset = so | frS, rset = ro | frR;
+                        const int exS = group_exclusive_scan<LPC>(__popcll(sset), gl);
+                        const int exR = group_exclusive_scan<LPC>(__popcll(rset), gl);
+                        sset = lowest_bits(sset, l - exS);                // first l entries of each list
+                        rset = lowest_bits(rset, l - exR);
+                        const T cj = last ? c.c_last : c.c_full, gj = last ? c.g_last : c.g_full;
+                        const T tc = t + cj, tr = tc + gj;
+                        if (!(tc > t)) status = PRS_CFG_STALLED;
+                        if (kSched) {                                     // e-th sender pairs with e-th receiver
+                            uint64_t m = sset;
+                            int e = exS;
+                            while (m) {
+                                const int b = __builtin_ctzll(m);
+                                m &= m - 1;
+                                const int64_t o = out_base + emitted + e;
+                                if (sched.src) sched.src[o] = gl * 64 + b;
+                                if (sched.seg) sched.seg[o] = j;
+                                if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                                ++e;
+                            }
+                            m = rset;
+                            e = exR;
+                            while (m) {
+                                const int b = __builtin_ctzll(m);
+                                m &= m - 1;
+                                if (sched.dst) sched.dst[out_base + emitted + e] = gl * 64 + b;
+                                ++e;
+                            }
+                        }
+                        emitted += l;
+                        row |= sset;
+                        sfree &= ~sset;
+                        rfree &= ~rset;
+                        uint64_t carry = sset;                            // count one more sent segment for the senders
+#pragma unroll
+                        for (int b = 0; b < kPlanes; ++b) { const uint64_t u = cnt[b] & carry; cnt[b] ^= carry; carry = u; }
+                        if (ng < kCap) {
+                            gS[(cur * kCap + ng) * kGroups + gw] = tc; gR[(cur * kCap + ng) * kGroups + gw] = tr;
+                            gSm[ng * kWave + lane] = sset; gRm[ng * kWave + lane] = rset;
+                            ++ng;
+                        } else {
+                            overflow = true;
+                        }
+                        if (tc < minNew) minNew = tc;
+                        if (tr < minNew) minNew = tr;
+                        cs -= l; cr -= l;
+                        remj -= l;
+                        if (remj == 0) {                                  // only the root is left: done after the last arrival
+                            if (tr > Tmax) Tmax = tr;
+                            ++ndone;
+                        }
+                    }
+                    if (gl < W && (l > 0 || j > jhi)) myrows[static_cast<size_t>(j) * LPC + gl] = row;
+                    if (j > jhi) jhi = j;
+                    ++j;
+                }
+            }
+        }
+    }
+}
+
+template <typename T, bool kSched, int LPC>
+static void launch_one(const BiGroupLaunch &L)
+{
+    hipLaunchKernelGGL((bi_group_kernel<T, kSched, LPC>), dim3(L.grid), dim3(kWave), bi_group_lds_bytes(LPC), L.stream, L.cfg,
+                       L.p_max, L.q_max, L.model, L.times, L.sched, L.plan, L.order, L.cls, L.retry, L.rows, L.rows_per_group);
+}
+
+template <typename T, bool kSched> static void launch_lpc(const BiGroupLaunch &L)
+{
+    if (L.lpc == 1) launch_one<T, kSched, 1>(L);
+    else if (L.lpc == 4) launch_one<T, kSched, 4>(L);
+    else launch_one<T, kSched, 16>(L);
+}
+
+hipError_t launch_bi_group(const BiGroupLaunch &L)
+{
+    if (L.cost == PRS_COST_I64) { if (L.want_schedule) launch_lpc<int64_t, true>(L); else launch_lpc<int64_t, false>(L); }
+    else { if (L.want_schedule) launch_lpc<double, true>(L); else launch_lpc<double, false>(L); }
+    return hipGetLastError();
+}
+
+}  // namespace prs

@@ -48,6 +48,25 @@ size_t uni_state_bytes(bool sched, int32_t p_cap);                 // all of uni
 size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lists, per-segment counters
 size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
 size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
+// Several configurations per wavefront (p <= 1024, q <= 1023): lpc lanes per configuration.
+struct BiGroupLaunch {
+    ConfigArrays cfg;
+    int32_t p_max, q_max;
+    int model, cost;
+    bool want_schedule;
+    TimesOut times;
+    SchedOut sched;
+    PlanHeader *plan;
+    const int32_t *order;
+    int cls, lpc;
+    int32_t *retry;
+    uint64_t *rows;
+    size_t rows_per_group;
+    int grid;
+    hipStream_t stream;
+};
+size_t bi_group_lds_bytes(int lpc);
+hipError_t launch_bi_group(const BiGroupLaunch &L);
 hipError_t launch_uni(const UniLaunch &L);
 hipError_t launch_bi(const BiLaunch &L);
 

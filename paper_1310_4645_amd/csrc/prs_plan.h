@@ -9,17 +9,19 @@ namespace prs {
 
 constexpr int kClasses = 4;          // three LDS classes by p, one class with state in global memory
 constexpr int kWorkBuckets = 40;     // floor(log2(work)) buckets, heaviest first
+constexpr int kRetryClass = kClasses; // pseudo class: configurations handed back to the general kernel
 
 struct PlanHeader {
-    unsigned long long ticket[kClasses];
-    int32_t class_begin[kClasses];
-    int32_t class_count[kClasses];
+    unsigned long long ticket[kClasses + 1];
+    int32_t class_begin[kClasses + 1];
+    int32_t class_count[kClasses + 1];
     int32_t hist[kClasses * kWorkBuckets];
     int32_t start[kClasses * kWorkBuckets];
     int32_t cursor[kClasses * kWorkBuckets];
 };
 
-struct ClassLimits { int32_t p[kClasses - 1]; };     // class k holds p <= limits.p[k]; the last class the rest
+// class k holds p <= limits.p[k]; the last class the rest and every configuration with more than q segments
+struct ClassLimits { int32_t p[kClasses - 1]; int32_t q; };
 
 struct PlanLaunch {
     ConfigArrays cfg;

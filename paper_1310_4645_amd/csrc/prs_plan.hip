@@ -10,7 +10,7 @@ __device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, i
     if (c.status != PRS_CFG_OK) return kWorkBuckets - 1;                 // nothing to do: lightest bucket of class 0
     int cls = kClasses - 1;
     for (int k = kClasses - 2; k >= 0; --k)
-        if (c.p <= lim.p[k]) cls = k;
+        if (c.p <= lim.p[k] && c.q <= lim.q) cls = k;
     const int64_t work = static_cast<int64_t>(c.p - 1) * c.q;
     int lg = 63 - __builtin_clzll(static_cast<unsigned long long>(work) | 1ULL);
     if (lg > kWorkBuckets - 1) lg = kWorkBuckets - 1;
@@ -20,7 +20,7 @@ __device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, i
 __global__ void plan_clear(PlanHeader *h)
 {
     const int i = threadIdx.x;
-    if (i < kClasses) { h->ticket[i] = 0ULL; h->class_begin[i] = 0; h->class_count[i] = 0; }
+    if (i < kClasses + 1) { h->ticket[i] = 0ULL; h->class_begin[i] = 0; h->class_count[i] = 0; }
     for (int k = i; k < kClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
 }
 
