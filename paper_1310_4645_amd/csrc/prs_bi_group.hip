@@ -58,6 +58,46 @@ template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, in
     return inc - v;
 }
 
+template <int LPC> __device__ __forceinline__ int group_min(int v)
+{
+#pragma unroll
+    for (int o = LPC / 2; o > 0; o >>= 1) {
+        const int u = __shfl_xor(v, o, LPC);
+        v = u < v ? u : v;
+    }
+    return v;
+}
+
+constexpr int kNoSegment = 1 << 20;
+
+// Smallest value of a bit-sliced counter over the processors in `set` (kNoSegment if the set is empty):
+// walk the planes from the top, keeping the members whose bit can still be 0.
+__device__ __forceinline__ int sliced_min(const uint64_t (&plane)[kPlanes], uint64_t set)
+{
+    if (set == 0) return kNoSegment;
+    int v = 0;
+#pragma unroll
+    for (int b = kPlanes - 1; b >= 0; --b) {
+        const uint64_t zero = set & ~plane[b];
+        if (zero) set = zero; else v |= 1 << b;
+    }
+    return v;
+}
+
+// processors of `set` whose bit-sliced counter equals v
+__device__ __forceinline__ uint64_t sliced_equal(const uint64_t (&plane)[kPlanes], uint64_t set, int v)
+{
+#pragma unroll
+    for (int b = 0; b < kPlanes; ++b) set &= ((v >> b) & 1) ? plane[b] : ~plane[b];
+    return set;
+}
+
+__device__ __forceinline__ void sliced_increment(uint64_t (&plane)[kPlanes], uint64_t who)
+{
+#pragma unroll
+    for (int b = 0; b < kPlanes; ++b) { const uint64_t u = plane[b] & who; plane[b] ^= who; who = u; }
+}
+
 template <typename T, bool kSched, int LPC>
 __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
                                                          TimesOut times, SchedOut sched, PlanHeader *plan,
@@ -96,10 +136,10 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
     bool need_event = true, overflow = false;
     int64_t emitted = 0, out_base = 0, events = 0;
     uint64_t valid = 0, sfree = 0, rfree = 0, compF = 0, compL = 0;   // this lane's word
-    uint64_t cnt[kPlanes];
+    uint64_t cnt[kPlanes];      // bit-sliced: segments sent per processor
+    uint64_t nxt_seg[kPlanes];  // bit-sliced: a segment index below which the processor has sent everything
 #pragma unroll
-    for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
-    int cs = 0, cr = 0;
+    for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
     c.p = 2; c.q = 1; c.status = 0; c.c_full = c.c_last = c.g_full = c.g_last = 0;
 
     for (;;) {
@@ -127,7 +167,7 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                 t = 0; Tmax = 0; minNew = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
                 need_event = true; overflow = false; emitted = 0; events = 0;
 #pragma unroll
-                for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
+                for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
             }
         }
         // wavefront-wide exit: every group out of tickets and idle
@@ -197,8 +237,6 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
             sfree = live & ~rootbit & ~sbusy;                             // the root never sends
             rfree = live & ~rbusy;
             compF = cF; compL = cL;
-            cs = group_sum<LPC>(__popcll(sfree & ~compL));
-            cr = group_sum<LPC>(__popcll(rfree & ~compL));
             j = segStart;
             need_event = false;
         }
@@ -206,7 +244,20 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
         // ---------------------------------------------------------------- one visit (t, j)
         const bool visit = run && !need_event && status == PRS_CFG_OK;
         if (visit) {
-            if (j >= c.q || cs == 0 || cr == 0) {
+            // A pair for segment j needs a processor with a free send port and one with a free receive
+            // port that both still hold j.  nxt_seg bounds from below the first segment a processor still
+            // holds (the root holds every unfinished one), so segments below both bounds are skipped.
+            {
+                const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
+                const uint64_t as = sfree & ~compL, ar = rfree & ~compL;
+                const int js = group_min<LPC>(sliced_min(nxt_seg, as));
+                int jr = sliced_min(nxt_seg, ar & ~rootbit);
+                if (ar & rootbit) jr = jr < segStart ? jr : segStart;
+                jr = group_min<LPC>(jr);
+                const int jn = js > jr ? js : jr;
+                if (jn > j) j = jn;
+            }
+            if (j >= c.q) {
                 need_event = true;                                        // nothing more can pair at this t
             } else {
                 const bool last = j == c.q - 1;
@@ -214,6 +265,8 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                 if (j <= jhi && gl < W) row = myrows[static_cast<size_t>(j) * LPC + gl];
                 const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
                 const uint64_t memb = ~row & valid;                       // still hold segment j (root: until done)
+                // a processor whose bound points at j but has sent j already: the bound moves up
+                sliced_increment(nxt_seg, sliced_equal(nxt_seg, row & valid, j));
                 int remj = group_sum<LPC>(__popcll(memb & ~rootbit));
                 if (remj == 0) {                                          // everybody has sent segment j
                     if (j == segStart) ++segStart;
@@ -273,9 +326,8 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                         row |= sset;
                         sfree &= ~sset;
                         rfree &= ~rset;
-                        uint64_t carry = sset;                            // count one more sent segment for the senders
-#pragma unroll
-                        for (int b = 0; b < kPlanes; ++b) { const uint64_t u = cnt[b] & carry; cnt[b] ^= carry; carry = u; }
+                        sliced_increment(cnt, sset);                     // one more sent segment for the senders
+                        sliced_increment(nxt_seg, sliced_equal(nxt_seg, sset, j));
                         if (ng < kCap) {
                             gS[(cur * kCap + ng) * kGroups + gw] = tc; gR[(cur * kCap + ng) * kGroups + gw] = tr;
                             gSm[ng * kWave + lane] = sset; gRm[ng * kWave + lane] = rset;
@@ -285,7 +337,6 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                         }
                         if (tc < minNew) minNew = tc;
                         if (tr < minNew) minNew = tr;
-                        cs -= l; cr -= l;
                         remj -= l;
                         if (remj == 0) {                                  // only the root is left: done after the last arrival
                             if (tr > Tmax) Tmax = tr;
