@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
     int W = 0;
     T t = 0, Tmax = 0, minNew = kInf;
     int ndone = 0, segStart = 0, j = 0, jhi = -1, ng = 0, status = 0;
-    bool need_event = true, overflow = false;
+    bool need_event = true, overflow = false, idle_visit = false;
     int64_t emitted = 0, out_base = 0, events = 0;
     uint64_t valid = 0, sfree = 0, rfree = 0, compF = 0, compL = 0;   // this lane's word
     uint64_t cnt[kPlanes];      // bit-sliced: segments sent per processor
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                 valid = 0;
                 if (gl < W) valid = (gl == W - 1 && (c.p & 63)) ? (UINT64_C(1) << (c.p & 63)) - 1 : ~UINT64_C(0);
                 t = 0; Tmax = 0; minNew = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
-                need_event = true; overflow = false; emitted = 0; events = 0;
+                need_event = true; overflow = false; idle_visit = false; emitted = 0; events = 0;
 #pragma unroll
                 for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
             }
@@ -238,24 +238,47 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
             rfree = live & ~rbusy;
             compF = cF; compL = cL;
             j = segStart;
+            idle_visit = false;
             need_event = false;
         }
 
         // ---------------------------------------------------------------- one visit (t, j)
         const bool visit = run && !need_event && status == PRS_CFG_OK;
         if (visit) {
-            // A pair for segment j needs a processor with a free send port and one with a free receive
-            // port that both still hold j.  nxt_seg bounds from below the first segment a processor still
-            // holds (the root holds every unfinished one), so segments below both bounds are skipped.
+            // A pair for segment j needs a processor with a free send port and a different one with a free
+            // receive port that both still hold j and are not excluded by a computation.  nxt_seg bounds
+            // from below the first segment a processor still holds (the root holds every unfinished one),
+            // so segments below the larger of the two smallest bounds are skipped.  If a visit paired
+            // nobody although every candidate still held the segment, no later segment can pair either:
+            // its candidates are a subset.  Exclusion by a pending computation depends on tcomm(j),
+            // shorter for the last segment only: segments before the last use the full-length exclusion
+            // set, the last one its own.
             {
                 const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
-                const uint64_t as = sfree & ~compL, ar = rfree & ~compL;
-                const int js = group_min<LPC>(sliced_min(nxt_seg, as));
-                int jr = sliced_min(nxt_seg, ar & ~rootbit);
-                if (ar & rootbit) jr = jr < segStart ? jr : segStart;
-                jr = group_min<LPC>(jr);
-                const int jn = js > jr ? js : jr;
-                if (jn > j) j = jn;
+                int jn = kNoSegment;
+                if (!idle_visit) {
+                    const uint64_t as = sfree & ~compF, ar = rfree & ~compF;
+                    int v1 = sliced_min(nxt_seg, as);
+                    int v2 = sliced_min(nxt_seg, ar & ~rootbit);
+                    if (ar & rootbit) v2 = v2 < segStart ? v2 : segStart;
+                    int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
+                    v1 = group_min<LPC>(v1); v2 = group_min<LPC>(v2);
+                    ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
+                    nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
+                    const bool pairable = ns1 > 0 && nr1 > 0 && !(ns1 == 1 && nr1 == 1 && nb1 == 1);
+                    int cand = v1 > v2 ? v1 : v2;
+                    if (cand < j) cand = j;
+                    if (pairable && cand < c.q - 1) jn = cand;
+                }
+                if (jn == kNoSegment && j <= c.q - 1) {               // only the last segment is left to try
+                    const uint64_t as = sfree & ~compL, ar = rfree & ~compL;
+                    int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
+                    ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
+                    nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
+                    if (ns1 > 0 && nr1 > 0 && !(ns1 == 1 && nr1 == 1 && nb1 == 1)) jn = c.q - 1;
+                }
+                j = jn == kNoSegment ? c.q : jn;
+                idle_visit = false;
             }
             if (j >= c.q) {
                 need_event = true;                                        // nothing more can pair at this t
@@ -346,6 +369,8 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
                     if (gl < W && (l > 0 || j > jhi)) myrows[static_cast<size_t>(j) * LPC + gl] = row;
                     if (j > jhi) jhi = j;
                     ++j;
+                    // nobody paired and no candidate had already sent j
+                    idle_visit = l == 0 && group_sum<LPC>(((sfree | rfree) & ~comp & row) != 0 ? 1 : 0) == 0;
                 }
             }
         }
