@@ -64,18 +64,27 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 }
 
 // ---- size classes and workspace layout (shared by prs_workspace_bytes and the launches) --------------
-constexpr int32_t kClassP[kClasses - 1] = {64, 256, 1024};   // p limits of the LDS classes
+//
+// A batch is split into four classes, each run by the kernel and the LDS allocation that fit it:
+//   uni-greedy, completion times:  p <= 256 and p <= 1024 with few segments: batch kernel, state in LDS;
+//                                  every configuration with at least kPipeMinQ segments: one lane per
+//                                  segment; the rest (p > 1024, few segments): batch kernel, state in the
+//                                  workspace;
+//   uni-greedy, schedules:         batch kernel with state in LDS for p <= 64 / 256 / 1024, else workspace;
+//   bi-greedy:                     1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
+//                                  q <= 1023; the general kernel for the rest and for reruns.
+enum ClassKind { kUniBatch, kUniPipe, kBiGroup, kBiGeneral };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
-
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
-constexpr int kGroupLpc[kClasses - 1] = {1, 4, 16};
+constexpr int32_t kPipeMinQ = 8;       // fewer segments than this leave most lanes of the per-segment kernel idle
 
 struct ClassSpec {
-    int lpc;                  // > 0: bi-greedy, several configurations per wavefront, lpc lanes each
-    size_t rows_per_group;    // words of sent-bit rows per configuration slot
+    ClassKind kind;
+    int lpc;                  // kBiGroup: lanes per configuration
+    size_t rows_per_group;    // kBiGroup: words of sent-bit rows per configuration slot
     int32_t p_cap;            // capacity of the per-processor arrays of this class
-    bool lds;                 // state (uni) / small arrays and maybe the bitmap (bi) in LDS
+    bool lds;                 // state (uni batch) / small arrays and maybe the bitmap (bi general) in LDS
     size_t lds_bytes;
     int32_t lds_bitmap_bytes;
     size_t slot_bytes, slot_offset;
@@ -84,6 +93,7 @@ struct ClassSpec {
 
 struct Layout {
     size_t header, order, retry, total;
+    ClassLimits limits;
     ClassSpec cls[kClasses];
 };
 
@@ -97,25 +107,45 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.order = plan_header_bytes();
     L.retry = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     size_t off = L.retry + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
+    // which configurations go where
+    const bool pipe = model == PRS_UNI && !sched;
+    const int32_t plim_pipe[kClasses - 1] = {256, 1024, 0}, plim_std[kClasses - 1] = {64, 256, 1024};
+    for (int k = 0; k < kClasses - 1; ++k) L.limits.p[k] = pipe ? plim_pipe[k] : plim_std[k];
+    L.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
+    L.limits.pipe_min_q = pipe ? kPipeMinQ : INT32_MAX;
+    L.limits.pipe_cls = pipe ? kClasses - 2 : -1;
+    static const int group_lpc[kClasses - 1] = {1, 4, 16};
     for (int k = 0; k < kClasses; ++k) {
         ClassSpec &c = L.cls[k];
         const bool last = k == kClasses - 1;
-        c.p_cap = last ? p_max : (kClassP[k] < p_max ? kClassP[k] : p_max);
+        const bool is_pipe = pipe && k == L.limits.pipe_cls;
+        c.p_cap = (last || is_pipe) ? p_max : (L.limits.p[k] < p_max ? L.limits.p[k] : p_max);
         c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
-        if (model == PRS_BI && !last) {
+        bool possible = last || is_pipe || k == 0 || L.limits.p[k - 1] < p_max;   // can a configuration land here?
+        if (is_pipe) {
+            c.kind = kUniPipe;
+            c.lds = true;
+            c.lds_bytes = uni_pipe_lds_bytes();
+            c.slot_bytes = uni_pipe_slot_bytes(c.p_cap);
+            possible = q_max >= kPipeMinQ;
+        } else if (model == PRS_UNI) {
+            c.kind = kUniBatch;
+            const size_t st = uni_state_bytes(sched, c.p_cap);
+            if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
+            else c.slot_bytes = st;
+            if (last) possible = p_max > L.limits.p[pipe ? 1 : kClasses - 2];
+        } else if (!last) {
             // several configurations per wavefront; the slot of a wavefront holds the sent-bit rows of its groups
-            c.lpc = kGroupLpc[k];
+            c.kind = kBiGroup;
+            c.lpc = group_lpc[k];
             c.lds = true;
             c.lds_bytes = bi_group_lds_bytes(c.lpc);
             const int32_t q_cap = q_max < kGroupQMax ? q_max : kGroupQMax;
             c.rows_per_group = static_cast<size_t>(q_cap) * c.lpc;
             c.slot_bytes = c.rows_per_group * 8 * (64 / c.lpc);
-        } else if (model == PRS_UNI) {
-            const size_t st = uni_state_bytes(sched, c.p_cap);
-            if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
-            else c.slot_bytes = st;
         } else {
             // general one-configuration-per-wavefront kernel: big p or many segments, and reruns
+            c.kind = kBiGeneral;
             const size_t small = bi_small_bytes(c.p_cap, q_max), bitmap = bi_bitmap_bytes(c.p_cap, q_max);
             if (small <= kLdsPerBlockMax / 2) {
                 c.lds = true;
@@ -132,10 +162,10 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
             g = per_cu * kCUs;
         } else {
             g = kGlobalClassGrid;
-            while (g > 256 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;   // big slots: fewer resident blocks
         }
+        while (g > 256 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;   // big slots: fewer resident blocks
         if (g > n) g = n < 1 ? 1 : n;
-        if (k > 0 && kClassP[k - 1] >= p_max && !(model == PRS_BI && last)) g = 0;      // p_max rules this class out
+        if (!possible) g = 0;
         c.grid = static_cast<int>(g);
         c.slot_offset = off;
         off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
@@ -166,18 +196,36 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
     PlanLaunch P;
     P.cfg = ConfigArrays{cfg->p, cfg->q_req, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
     P.n = n; P.p_max = p_max; P.q_max = q_max; P.cost = cost;
-    for (int k = 0; k < kClasses - 1; ++k) P.limits.p[k] = kClassP[k];
-    P.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
+    P.limits = lay.limits;
     P.header = reinterpret_cast<PlanHeader *>(ws + lay.header);
     P.order = reinterpret_cast<int32_t *>(ws + lay.order);
     P.stream = st;
     if (launch_plan(P) != hipSuccess) return PRS_EDEVICE;
     int32_t *retry = reinterpret_cast<int32_t *>(ws + lay.retry);
-    // heaviest class first; a class without configurations ends at once
+    auto general = [&](int k, const int32_t *order, int cls) {          // batch / general kernels
+        const ClassSpec &c = lay.cls[k];
+        UniLaunch L;
+        L.cfg = P.cfg;
+        L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
+        L.want_schedule = call == PRS_CALL_SCHEDULE;
+        L.times = times; L.sched = sched;
+        L.plan = P.header; L.order = order; L.cls = cls;
+        L.lds_p = c.lds ? c.p_cap : 0;
+        L.lds_bitmap_bytes = c.lds_bitmap_bytes;
+        L.lds_bytes = c.lds_bytes;
+        L.slots = ws + c.slot_offset;
+        L.slot_bytes = c.slot_bytes;
+        L.slot_p = c.p_cap; L.slot_q = q_max;
+        L.grid = c.grid;
+        L.stream = st;
+        if (c.kind == kUniPipe) return launch_uni_pipe(L);
+        return model == PRS_UNI ? launch_uni(L) : launch_bi(L);
+    };
+    // the class with the longest-running configurations first; a class without configurations ends at once
     for (int k = kClasses - 1; k >= 0; --k) {
         const ClassSpec &c = lay.cls[k];
         if (c.grid == 0) continue;                       // no configuration can fall in this class
-        if (c.lpc > 0) {
+        if (c.kind == kBiGroup) {
             BiGroupLaunch G;
             G.cfg = P.cfg; G.p_max = p_max; G.q_max = q_max; G.model = model; G.cost = cost;
             G.want_schedule = call == PRS_CALL_SCHEDULE;
@@ -187,44 +235,12 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             G.rows_per_group = c.rows_per_group;
             G.grid = c.grid; G.stream = st;
             if (launch_bi_group(G) != hipSuccess) return PRS_EDEVICE;
-            continue;
+        } else if (general(k, P.order, k) != hipSuccess) {
+            return PRS_EDEVICE;
         }
-        UniLaunch L;
-        L.cfg = P.cfg;
-        L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
-        L.want_schedule = call == PRS_CALL_SCHEDULE;
-        L.times = times; L.sched = sched;
-        L.plan = P.header; L.order = P.order; L.cls = k;
-        L.lds_p = c.lds ? c.p_cap : 0;
-        L.lds_bitmap_bytes = c.lds_bitmap_bytes;
-        L.lds_bytes = c.lds_bytes;
-        L.slots = ws + c.slot_offset;
-        L.slot_bytes = c.slot_bytes;
-        L.slot_p = c.p_cap; L.slot_q = q_max;
-        L.grid = c.grid;
-        L.stream = st;
-        const hipError_t err = model == PRS_UNI ? launch_uni(L) : launch_bi(L);
-        if (err != hipSuccess) return PRS_EDEVICE;
     }
-    if (model == PRS_BI) {
-        // configurations whose list of running groups did not fit go through the general kernel
-        const ClassSpec &c = lay.cls[kClasses - 1];
-        UniLaunch L;
-        L.cfg = P.cfg;
-        L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
-        L.want_schedule = call == PRS_CALL_SCHEDULE;
-        L.times = times; L.sched = sched;
-        L.plan = P.header; L.order = retry; L.cls = kRetryClass;
-        L.lds_p = c.lds ? c.p_cap : 0;
-        L.lds_bitmap_bytes = c.lds_bitmap_bytes;
-        L.lds_bytes = c.lds_bytes;
-        L.slots = ws + c.slot_offset;
-        L.slot_bytes = c.slot_bytes;
-        L.slot_p = c.p_cap; L.slot_q = q_max;
-        L.grid = c.grid;
-        L.stream = st;
-        if (launch_bi(L) != hipSuccess) return PRS_EDEVICE;
-    }
+    // configurations whose list of running groups did not fit go through the general kernel
+    if (model == PRS_BI && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
     return PRS_OK;
 }
 

@@ -21,7 +21,9 @@ struct PlanHeader {
 };
 
 // class k holds p <= limits.p[k]; the last class the rest and every configuration with more than q segments
-struct ClassLimits { int32_t p[kClasses - 1]; int32_t q; };
+// Configurations with at least pipe_min_q segments go to class pipe_cls whatever their p (disabled when
+// pipe_cls < 0).
+struct ClassLimits { int32_t p[kClasses - 1]; int32_t q; int32_t pipe_min_q; int32_t pipe_cls; };
 
 struct PlanLaunch {
     ConfigArrays cfg;
