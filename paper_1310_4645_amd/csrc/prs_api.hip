@@ -108,7 +108,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.retry = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     size_t off = L.retry + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     // which configurations go where
-    const bool pipe = model == PRS_UNI && !sched;
+    const bool pipe = model == PRS_UNI;
     const int32_t plim_pipe[kClasses - 1] = {256, 1024, 0}, plim_std[kClasses - 1] = {64, 256, 1024};
     for (int k = 0; k < kClasses - 1; ++k) L.limits.p[k] = pipe ? plim_pipe[k] : plim_std[k];
     L.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
@@ -125,15 +125,16 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         if (is_pipe) {
             c.kind = kUniPipe;
             c.lds = true;
-            c.lds_bytes = uni_pipe_lds_bytes();
-            c.slot_bytes = uni_pipe_slot_bytes(c.p_cap);
+            c.p_cap = (c.p_cap + 3) / 4 * 4;                     // keeps every per-lane array 8-byte aligned
+            c.lds_bytes = sched ? uni_pipe_sched_lds_bytes() : uni_pipe_lds_bytes();
+            c.slot_bytes = sched ? uni_pipe_sched_slot_bytes(c.p_cap) : uni_pipe_slot_bytes(c.p_cap);
             possible = q_max >= kPipeMinQ;
         } else if (model == PRS_UNI) {
             c.kind = kUniBatch;
             const size_t st = uni_state_bytes(sched, c.p_cap);
             if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
             else c.slot_bytes = st;
-            if (last) possible = p_max > L.limits.p[pipe ? 1 : kClasses - 2];
+            if (last) possible = sched || p_max > L.limits.p[pipe ? 1 : kClasses - 2];   // schedules: also the rerun path
         } else if (!last) {
             // several configurations per wavefront; the slot of a wavefront holds the sent-bit rows of its groups
             c.kind = kBiGroup;
@@ -218,7 +219,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         L.slot_p = c.p_cap; L.slot_q = q_max;
         L.grid = c.grid;
         L.stream = st;
-        if (c.kind == kUniPipe) return launch_uni_pipe(L);
+        if (c.kind == kUniPipe) return L.want_schedule ? launch_uni_pipe_sched(L, retry) : launch_uni_pipe(L);
         return model == PRS_UNI ? launch_uni(L) : launch_bi(L);
     };
     // the class with the longest-running configurations first; a class without configurations ends at once
@@ -240,7 +241,8 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         }
     }
     // configurations whose list of running groups did not fit go through the general kernel
-    if (model == PRS_BI && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
+    // (bi-greedy) and schedules in which equal rounded sums upset the index order (uni-greedy) are rerun
+    if ((model == PRS_BI || call == PRS_CALL_SCHEDULE) && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
     return PRS_OK;
 }
 

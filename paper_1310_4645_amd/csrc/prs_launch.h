@@ -71,6 +71,9 @@ hipError_t launch_uni(const UniLaunch &L);
 size_t uni_pipe_lds_bytes();
 size_t uni_pipe_slot_bytes(int32_t p_cap);
 hipError_t launch_uni_pipe(const UniLaunch &L);
+size_t uni_pipe_sched_lds_bytes();
+size_t uni_pipe_sched_slot_bytes(int32_t p_cap);
+hipError_t launch_uni_pipe_sched(const UniLaunch &L, int32_t *retry);
 hipError_t launch_bi(const BiLaunch &L);
 
 struct ReplayLaunch {

@@ -162,6 +162,254 @@ __global__ __launch_bounds__(kWave) void uni_pipe_kernel(ConfigArrays cfg, int32
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same pipeline with processor identities: emits the pairs (Section 5, first paragraph) in the
+// order of Algorithm 1, ties by processor index, the root never sending.
+//
+// Differences to the value-only kernel:
+//  - stream entries are (value, sender index) and must reach the next segment sorted by both.  Senders
+//    of one start time leave with equal values and rising indices, except that the first pair of such a
+//    run may be led by a processor left over from a smaller value.  The producer therefore holds back
+//    the entry with the largest index of the running value and writes the others; the next segment only
+//    reads entries below the running value (they are final), so the order inside the run can still change.
+//  - the root's final state (largest value, index 0) is a third source next to A and B: it sorts before
+//    stream entries of equal value.
+//  - B needs the receiver's index per pair, kept in a per-lane array; its values are still S + tcomp.
+//  - sums produced at different times that round to the same double could break the index order inside
+//    a run in a way the hold-back does not repair; such a configuration (none in the sweeps) is handed
+//    to the batch kernel.
+constexpr int kRingS = 16;
+
+size_t uni_pipe_sched_lds_bytes() { return static_cast<size_t>(kRingS) * kWave * 16; }
+size_t uni_pipe_sched_slot_bytes(int32_t p_cap)
+{
+    return static_cast<size_t>(kWave) * (2 * static_cast<size_t>(p_cap) * 12 + static_cast<size_t>(p_cap) * 4);
+}
+
+template <typename T> __device__ __forceinline__ bool klt(T xa, int32_t ia, T xb, int32_t ib)
+{
+    return xa < xb || (xa == xb && ia < ib);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, SchedOut sched,
+                                                               PlanHeader *plan, const int32_t *order, int cls, int32_t *retry,
+                                                               char *slots, size_t slot_bytes, int32_t slot_p)
+{
+    PRS_DYNAMIC_LDS(lds_raw);
+    T *ringX = reinterpret_cast<T *>(lds_raw);                                   // [kRingS][64] stream values
+    int32_t *ringI = reinterpret_cast<int32_t *>(ringX + kRingS * kWave);        // [kRingS][64] stream sender indices
+    int32_t *ringB = ringI + kRingS * kWave;                                     // [kRingS][64] receiver index per pair
+    const int lane = lane_id();
+    const int prod = (lane + kWave - 1) & (kWave - 1), cons = (lane + 1) & (kWave - 1);
+    char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
+    const size_t per_lane = 2 * static_cast<size_t>(slot_p) * 12 + static_cast<size_t>(slot_p) * 4;
+    auto bufX = [&](int l, int par) { return reinterpret_cast<T *>(slot + l * per_lane + static_cast<size_t>(par) * slot_p * 8); };
+    auto bufI = [&](int l, int par) {
+        return reinterpret_cast<int32_t *>(slot + l * per_lane + 2 * static_cast<size_t>(slot_p) * 8 + static_cast<size_t>(par) * slot_p * 4);
+    };
+    int32_t *bufB = reinterpret_cast<int32_t *>(slot + lane * per_lane + 2 * static_cast<size_t>(slot_p) * 12);
+    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+
+    for (;;) {
+        const int64_t ticket = next_ticket(&plan->ticket[cls]);
+        if (ticket >= count) break;
+        const int64_t ci = order[begin + ticket];
+        const Config<T> c = decode_config<T>(cfg, ci, p_max, q_max);
+        int32_t status = c.status;
+        int64_t out_base = 0;
+        if (status == PRS_CFG_OK) {
+            out_base = sched.pair_offset[ci];
+            const int64_t n_pairs = static_cast<int64_t>(c.p - 1) * c.q;
+            if (out_base < 0 || out_base + n_pairs > sched.pair_capacity) status = PRS_CFG_TOO_LARGE;
+        }
+        T final_time = CostTraits<T>::bad();
+        bool rerun = false;
+        if (status == PRS_CFG_OK) {
+            const int p = c.p, q = c.q;
+            int k = lane, par = 0;
+            int ia = 0, ib = 0, ns = 0;          // stream entries read, B entries read, pairs done
+            int w = 0, runStart = 0;             // stream entries written, first entry of the running value
+            bool ha0 = false, ha1 = false, hb0 = false, hb1 = false, rootUsed = false;
+            T a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+            int32_t a0i = 0, a1i = 0, b0i = 0, b1i = 0;
+            bool hold = false;                   // entry of the running value held back (largest index so far)
+            T holdX = 0; int32_t holdI = 0, lastWI = -1;   // lastWI: index written last within the running value
+            T lastS = 0;                         // running value of my stream
+            T lastBx = 0; int32_t lastBi = -1;   // last B entry pushed
+            T prevRoot = 0;
+            int fin = -1;
+            int wtot = 0, segBase = 0, prevSegBase = 0, btot = 0, bsegBase = 0;
+            T cc = c.c(k < q ? k : 0), gg = c.g(k < q ? k : 0);
+            T result = 0;
+            bool bad = false;
+            for (;;) {
+                const bool active = k < q;
+                if (ballot64(active) == 0) break;
+                const int pk = __shfl(k, prod, kWave), prun = __shfl(runStart, prod, kWave), pfin = __shfl(fin, prod, kWave);
+                const int pwtot = __shfl(wtot, prod, kWave), pbase = __shfl(segBase, prod, kWave),
+                          pprevbase = __shfl(prevSegBase, prod, kWave);
+                const T plast = __shfl(lastS, prod, kWave), proot = __shfl(prevRoot, prod, kWave);
+                const int cfin = __shfl(fin, cons, kWave);
+                // stream entries below the producer's running value are final
+                int avail = 0;
+                bool complete = false;
+                T front = 0;
+                int abase = 0;
+                if (active) {
+                    if (k == 0 || pfin >= k - 1) { avail = p - 1; complete = true; abase = pk == k - 1 ? pbase : pprevbase; }
+                    else if (pk == k - 1) { avail = prun; front = plast; abase = pbase; }
+                }
+                const int apar = ((k - 1) >> 6) & 1;
+                const bool wa0 = active && !ha0 && ia < avail, wa1 = active && !ha1 && ia + 1 < avail;
+                const bool wb0 = active && !hb0 && ib < ns, wb1 = active && !hb1 && ib + 1 < ns;
+                // (the producer writes up to two entries per iteration; entries that close to being overwritten are
+                // read from the workspace so that the outcome does not depend on lanes running in lockstep)
+                const bool ga0 = wa0 && k > 0 && pwtot - (abase + ia) > kRingS - 2;
+                const bool ga1 = wa1 && k > 0 && pwtot - (abase + ia + 1) > kRingS - 2;
+                // B value i is stream value i (still in a register if not written yet); its index is in ringB / bufB
+                const bool gbx0 = wb0 && ib < w && wtot - (segBase + ib) > kRingS - 1;
+                const bool gbx1 = wb1 && ib + 1 < w && wtot - (segBase + ib + 1) > kRingS - 1;
+                const bool gbi0 = wb0 && btot - (bsegBase + ib) > kRingS - 1, gbi1 = wb1 && btot - (bsegBase + ib + 1) > kRingS - 1;
+                if (ballot64(ga0 || ga1 || gbx0 || gbx1 || gbi0 || gbi1) != 0)
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                if (wa0) {
+                    if (k == 0) { a0 = 0; a0i = ia + 1; }                 // first segment: processors 1..p-1 at time 0
+                    else if (ga0) { a0 = bufX(prod, apar)[ia]; a0i = bufI(prod, apar)[ia]; }
+                    else { const int r = ((abase + ia) & (kRingS - 1)) * kWave + prod; a0 = ringX[r]; a0i = ringI[r]; }
+                    ha0 = true;
+                }
+                if (wa1) {
+                    if (k == 0) { a1 = 0; a1i = ia + 2; }
+                    else if (ga1) { a1 = bufX(prod, apar)[ia + 1]; a1i = bufI(prod, apar)[ia + 1]; }
+                    else { const int r = ((abase + ia + 1) & (kRingS - 1)) * kWave + prod; a1 = ringX[r]; a1i = ringI[r]; }
+                    ha1 = true;
+                }
+                if (wb0) {
+                    T sx = lastS;
+                    if (ib < w) sx = gbx0 ? bufX(lane, par)[ib] : ringX[((segBase + ib) & (kRingS - 1)) * kWave + lane];
+                    b0 = sx + gg;
+                    b0i = gbi0 ? bufB[ib] : ringB[((bsegBase + ib) & (kRingS - 1)) * kWave + lane];
+                    hb0 = true;
+                }
+                if (wb1) {
+                    T sx = lastS;
+                    if (ib + 1 < w) sx = gbx1 ? bufX(lane, par)[ib + 1] : ringX[((segBase + ib + 1) & (kRingS - 1)) * kWave + lane];
+                    b1 = sx + gg;
+                    b1i = gbi1 ? bufB[ib + 1] : ringB[((bsegBase + ib + 1) & (kRingS - 1)) * kWave + lane];
+                    hb1 = true;
+                }
+                // the root of this segment: at time 0 in the first segment, else the previous segment's root
+                const bool hr = active && !rootUsed && (k == 0 || complete);
+                const T rx = k == 0 ? 0 : proot;
+                // ---- two smallest keys among the heads of A and B and the root
+                int s1 = -1, s2 = -1;                  // 0: A, 1: B, 2: root
+                T e1x = 0, e2x = 0; int32_t e1i = 0, e2i = 0;
+                {
+                    T bx = 0; int32_t bi = 0;
+                    if (ha0) { s1 = 0; bx = a0; bi = a0i; }
+                    if (hb0 && (s1 < 0 || klt<T>(b0, b0i, bx, bi))) { s1 = 1; bx = b0; bi = b0i; }
+                    if (hr && (s1 < 0 || klt<T>(rx, 0, bx, bi))) { s1 = 2; bx = rx; bi = 0; }
+                    e1x = bx; e1i = bi;
+                    // second: heads after removing the first
+                    const bool ca = s1 == 0 ? ha1 : ha0, cb = s1 == 1 ? hb1 : hb0, cr = hr && s1 != 2;
+                    const T ax = s1 == 0 ? a1 : a0; const int32_t ai = s1 == 0 ? a1i : a0i;
+                    const T bbx = s1 == 1 ? b1 : b0; const int32_t bbi = s1 == 1 ? b1i : b0i;
+                    T cx = 0; int32_t cid = 0;
+                    if (ca) { s2 = 0; cx = ax; cid = ai; }
+                    if (cb && (s2 < 0 || klt<T>(bbx, bbi, cx, cid))) { s2 = 1; cx = bbx; cid = bbi; }
+                    if (cr && (s2 < 0 || klt<T>(rx, 0, cx, cid))) { s2 = 2; cx = rx; cid = 0; }
+                    e2x = cx; e2i = cid;
+                }
+                bool ok = s1 >= 0 && s2 >= 0;
+                if (ok && !complete && !(e2x < front)) ok = false;      // an entry not final yet could come first
+                if (ns == 0 && k >= 2 * kWave && cfin < k - 2 * kWave + 1) ok = false;
+                if (active && ok) {
+                    const T t = e2x, tc = t + cc, tr = tc + gg;
+                    int32_t snd = e1i, rcv = e2i;
+                    if (e1i == 0) { snd = e2i; rcv = 0; }                 // the root never sends (Lemma 1 (ii))
+                    const int64_t o = out_base + static_cast<int64_t>(k) * (p - 1) + ns;
+                    if (sched.src) sched.src[o] = snd;
+                    if (sched.dst) sched.dst[o] = rcv;
+                    if (sched.seg) sched.seg[o] = k;
+                    if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                    // ---- stream entry (tc, snd): keep the largest index of the running value back
+                    T wx = 0; int32_t wi = 0; bool wr = false;
+                    if (hold && tc == holdX) {
+                        if (snd > holdI) { wx = holdX; wi = holdI; holdI = snd; } else { wx = tc; wi = snd; }
+                        wr = true;
+                        if (wi < lastWI) bad = true;                      // only equal sums from different times get here
+                        lastWI = wi;
+                    } else {
+                        if (hold) { wx = holdX; wi = holdI; wr = true; }
+                        hold = true; holdX = tc; holdI = snd; lastWI = -1;
+                    }
+                    if (wr) {
+                        bufX(lane, par)[w] = wx; bufI(lane, par)[w] = wi;
+                        const int r = (wtot & (kRingS - 1)) * kWave + lane;
+                        ringX[r] = wx; ringI[r] = wi;
+                        ++w; ++wtot;
+                    }
+                    if (!(tc == lastS) || ns == 0) runStart = w;          // entries before the running value are final
+                    lastS = tc;
+                    // ---- B entry (tr, rcv) of pair ns
+                    if (ns > 0 && tr == lastBx && rcv < lastBi) bad = true;
+                    lastBx = tr; lastBi = rcv;
+                    bufB[ns] = rcv;
+                    ringB[(btot & (kRingS - 1)) * kWave + lane] = rcv;
+                    ++btot;
+                    // ---- consume
+                    if (s1 == 2 || s2 == 2) rootUsed = true;
+                    const int dA = (s1 == 0) + (s2 == 0), dB = (s1 == 1) + (s2 == 1);
+                    if (dA == 2) { ia += 2; ha0 = ha1 = false; }
+                    else if (dA == 1) { ia += 1; a0 = a1; a0i = a1i; ha0 = ha1; ha1 = false; }
+                    if (dB == 2) { ib += 2; hb0 = hb1 = false; }
+                    else if (dB == 1) { ib += 1; b0 = b1; b0i = b1i; hb0 = hb1; hb1 = false; }
+                    ++ns;
+                    const int live = ns - ib;
+                    if (live == 1) { b0 = tr; b0i = rcv; hb0 = true; }
+                    else if (live == 2) { b1 = tr; b1i = rcv; hb1 = true; }
+                    if (ns == p - 1) {                                    // segment done: flush, hand over
+                        bufX(lane, par)[w] = holdX; bufI(lane, par)[w] = holdI;
+                        const int r = (wtot & (kRingS - 1)) * kWave + lane;
+                        ringX[r] = holdX; ringI[r] = holdI;
+                        ++w; ++wtot;
+                        hold = false;
+                        prevRoot = tr; fin = k; result = tr;
+                        k += kWave; par ^= 1;
+                        ia = ib = ns = w = runStart = 0;
+                        ha0 = ha1 = hb0 = hb1 = rootUsed = false; lastS = 0; lastWI = -1; lastBi = -1;
+                        prevSegBase = segBase; segBase = wtot; bsegBase = btot;
+                        cc = c.c(k < q ? k : 0); gg = c.g(k < q ? k : 0);
+                    }
+                }
+            }
+            final_time = __shfl(result, (q - 1) & (kWave - 1), kWave);
+            rerun = ballot64(bad) != 0;
+        }
+        if (lane == 0) {                  // the only lane-dependent branch of the loop body
+            if (rerun) {
+                retry[atomicAdd(&plan->class_count[kRetryClass], 1)] = static_cast<int32_t>(ci);
+            } else {
+                if (sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = final_time;
+                if (sched.cfg_status) sched.cfg_status[ci] = status;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_uni_pipe_sched(const UniLaunch &L, int32_t *retry)
+{
+    if (L.cost == PRS_COST_I64)
+        hipLaunchKernelGGL((uni_pipe_sched_kernel<int64_t>), dim3(L.grid), dim3(kWave), uni_pipe_sched_lds_bytes(), L.stream, L.cfg,
+                           L.p_max, L.q_max, L.sched, L.plan, L.order, L.cls, retry, L.slots, L.slot_bytes, L.slot_p);
+    else
+        hipLaunchKernelGGL((uni_pipe_sched_kernel<double>), dim3(L.grid), dim3(kWave), uni_pipe_sched_lds_bytes(), L.stream, L.cfg,
+                           L.p_max, L.q_max, L.sched, L.plan, L.order, L.cls, retry, L.slots, L.slot_bytes, L.slot_p);
+    return hipGetLastError();
+}
+
 hipError_t launch_uni_pipe(const UniLaunch &L)
 {
     if (L.cost == PRS_COST_I64)

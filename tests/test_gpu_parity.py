@@ -157,15 +157,17 @@ def test_fp64_rounding_ties(prs, model):
     n = 69
     p = np.arange(2, 2 + n).astype(np.int32)
     cases = [(1.0, 0.0, 2.0 ** -52), (1.0, 0.0, 2.0 ** -53), (0.75, 2.0 ** -54, 2.0 ** -51), (1.0, 2.0 ** -30, 0.0)]
-    for al, be, ga in cases:
-        host = prs_inputs.SweepConfigs(p, np.full(n, 5, np.int32), np.full(n, 13, np.int64), np.full(n, al),
-                                       np.full(n, be), np.full(n, ga), "f64")
-        dev = prs.DeviceConfigs.from_host(host)
-        got = prs.simulate_completion_batch(dev, model, 128, 8)
-        _sync()
-        ref = O.simulate_batch(host, model)
-        assert np.array_equal(_np(got["greedy"]), ref.T_greedy), (al, be, ga)
-        _check_schedules(prs, host, model, 128, 8)
+    # few segments (batch kernels) and enough segments for the one-lane-per-segment kernels
+    for q, m in ((5, 13), (9, 29)):
+        for al, be, ga in cases:
+            host = prs_inputs.SweepConfigs(p, np.full(n, q, np.int32), np.full(n, m, np.int64), np.full(n, al),
+                                           np.full(n, be), np.full(n, ga), "f64")
+            dev = prs.DeviceConfigs.from_host(host)
+            got = prs.simulate_completion_batch(dev, model, 128, 16)
+            _sync()
+            ref = O.simulate_batch(host, model)
+            assert np.array_equal(_np(got["greedy"]), ref.T_greedy), (q, al, be, ga)
+            _check_schedules(prs, host, model, 128, 16)
 
 
 def test_invalid_configurations_are_reported_not_fatal(prs):

@@ -33,7 +33,7 @@ def test_workspace_sizes_are_monotone_and_bounded():
     assert w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 64, 8) <= w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 1024, 8)
     assert w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 1024, 8) < w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 4096, 8)
     assert w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10, 64, 8) < w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10, 64, 512)
-    assert w(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI, 1, 10, 4096, 8) > w(prs.PRS_CALL_SIMULATE, prs.PRS_UNI, 1, 10, 4096, 8)
+    assert w(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI, 1, 10, 1024, 8) < w(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI, 1, 10, 4096, 8)
     assert w(prs.PRS_CALL_SIMULATE, prs.PRS_BI, 1, 10_000, 65536, 4096) <= 20 << 30
     assert w(prs.PRS_CALL_REPLAY, 0, 0, 1, 256, 64) > 256 * 64 * 4
     assert w(99, 0, 0, 1, 256, 64) == 0 and w(0, 0, 0, -1, 256, 64) == 0
