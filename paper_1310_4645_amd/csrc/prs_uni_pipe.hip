@@ -234,15 +234,14 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
             T a0 = 0, a1 = 0, b0 = 0, b1 = 0;
             int32_t a0i = 0, a1i = 0, b0i = 0, b1i = 0;
             bool hold = false;                   // entry of the running value held back (largest index so far)
-            T holdX = 0; int32_t holdI = 0, lastWI = -1;   // lastWI: index written last within the running value
+            T holdX = 0; int32_t holdI = 0;
             T lastS = 0;                         // running value of my stream
-            T lastBx = 0; int32_t lastBi = -1;   // last B entry pushed
+            T lastBx = 0; int brun = 0;          // value of the last B entry pushed, first pair of that value
             T prevRoot = 0;
             int fin = -1;
             int wtot = 0, segBase = 0, prevSegBase = 0, btot = 0, bsegBase = 0;
             T cc = c.c(k < q ? k : 0), gg = c.g(k < q ? k : 0);
             T result = 0;
-            bool bad = false;
             for (;;) {
                 const bool active = k < q;
                 if (ballot64(active) == 0) break;
@@ -326,6 +325,7 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
                 if (ns == 0 && k >= 2 * kWave && cfin < k - 2 * kWave + 1) ok = false;
                 if (active && ok) {
                     const T t = e2x, tc = t + cc, tr = tc + gg;
+                    bool b_moved = false;
                     int32_t snd = e1i, rcv = e2i;
                     if (e1i == 0) { snd = e2i; rcv = 0; }                 // the root never sends (Lemma 1 (ii))
                     const int64_t o = out_base + static_cast<int64_t>(k) * (p - 1) + ns;
@@ -338,26 +338,45 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
                     if (hold && tc == holdX) {
                         if (snd > holdI) { wx = holdX; wi = holdI; holdI = snd; } else { wx = tc; wi = snd; }
                         wr = true;
-                        if (wi < lastWI) bad = true;                      // only equal sums from different times get here
-                        lastWI = wi;
                     } else {
                         if (hold) { wx = holdX; wi = holdI; wr = true; }
-                        hold = true; holdX = tc; holdI = snd; lastWI = -1;
+                        hold = true; holdX = tc; holdI = snd;
                     }
                     if (wr) {
-                        bufX(lane, par)[w] = wx; bufI(lane, par)[w] = wi;
-                        const int r = (wtot & (kRingS - 1)) * kWave + lane;
-                        ringX[r] = wx; ringI[r] = wi;
+                        // entries of the running value are written in rising index order; sums of different
+                        // times that round to the same value can bring a smaller index late: insert it
+                        // (the next segment does not read the running value yet)
+                        int at = w;
+                        while (at > runStart && bufI(lane, par)[at - 1] > wi) {
+                            const int32_t mv = bufI(lane, par)[at - 1];
+                            bufI(lane, par)[at] = mv;
+                            if (wtot + 1 - (segBase + at) <= kRingS) ringI[((segBase + at) & (kRingS - 1)) * kWave + lane] = mv;
+                            --at;
+                        }
+                        bufX(lane, par)[w] = wx; bufI(lane, par)[at] = wi;
+                        ringX[(wtot & (kRingS - 1)) * kWave + lane] = wx;
+                        if (wtot + 1 - (segBase + at) <= kRingS) ringI[((segBase + at) & (kRingS - 1)) * kWave + lane] = wi;
                         ++w; ++wtot;
                     }
                     if (!(tc == lastS) || ns == 0) runStart = w;          // entries before the running value are final
                     lastS = tc;
-                    // ---- B entry (tr, rcv) of pair ns
-                    if (ns > 0 && tr == lastBx && rcv < lastBi) bad = true;
-                    lastBx = tr; lastBi = rcv;
-                    bufB[ns] = rcv;
-                    ringB[(btot & (kRingS - 1)) * kWave + lane] = rcv;
-                    ++btot;
+                    // ---- B entry (tr, rcv) of pair ns; equal values keep rising index order (same remark)
+                    if (ns == 0 || !(tr == lastBx)) brun = ns;
+                    lastBx = tr;
+                    {
+                        int at = ns;
+                        const int lo = brun > ib ? brun : ib;
+                        while (at > lo && bufB[at - 1] > rcv) {
+                            const int32_t mv = bufB[at - 1];
+                            bufB[at] = mv;
+                            if (btot + 1 - (bsegBase + at) <= kRingS) ringB[((bsegBase + at) & (kRingS - 1)) * kWave + lane] = mv;
+                            --at;
+                        }
+                        bufB[at] = rcv;
+                        if (btot + 1 - (bsegBase + at) <= kRingS) ringB[((bsegBase + at) & (kRingS - 1)) * kWave + lane] = rcv;
+                        if (at != ns) { hb0 = hb1 = false; b_moved = true; }   // cached heads may have changed
+                        ++btot;
+                    }
                     // ---- consume
                     if (s1 == 2 || s2 == 2) rootUsed = true;
                     const int dA = (s1 == 0) + (s2 == 0), dB = (s1 == 1) + (s2 == 1);
@@ -367,10 +386,12 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
                     else if (dB == 1) { ib += 1; b0 = b1; b0i = b1i; hb0 = hb1; hb1 = false; }
                     ++ns;
                     const int live = ns - ib;
-                    if (live == 1) { b0 = tr; b0i = rcv; hb0 = true; }
-                    else if (live == 2) { b1 = tr; b1i = rcv; hb1 = true; }
+                    if (!b_moved) {
+                        if (live == 1) { b0 = tr; b0i = rcv; hb0 = true; }
+                        else if (live == 2) { b1 = tr; b1i = rcv; hb1 = true; }
+                    }
                     if (ns == p - 1) {                                    // segment done: flush, hand over
-                        bufX(lane, par)[w] = holdX; bufI(lane, par)[w] = holdI;
+                        bufX(lane, par)[w] = holdX; bufI(lane, par)[w] = holdI;   // the held index is the largest of its value
                         const int r = (wtot & (kRingS - 1)) * kWave + lane;
                         ringX[r] = holdX; ringI[r] = holdI;
                         ++w; ++wtot;
@@ -378,14 +399,13 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
                         prevRoot = tr; fin = k; result = tr;
                         k += kWave; par ^= 1;
                         ia = ib = ns = w = runStart = 0;
-                        ha0 = ha1 = hb0 = hb1 = rootUsed = false; lastS = 0; lastWI = -1; lastBi = -1;
+                        ha0 = ha1 = hb0 = hb1 = rootUsed = false; lastS = 0; brun = 0;
                         prevSegBase = segBase; segBase = wtot; bsegBase = btot;
                         cc = c.c(k < q ? k : 0); gg = c.g(k < q ? k : 0);
                     }
                 }
             }
             final_time = __shfl(result, (q - 1) & (kWave - 1), kWave);
-            rerun = ballot64(bad) != 0;
         }
         if (lane == 0) {                  // the only lane-dependent branch of the loop body
             if (rerun) {
