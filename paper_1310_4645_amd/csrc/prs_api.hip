@@ -223,18 +223,26 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         return model == PRS_UNI ? launch_uni(L) : launch_bi(L);
     };
     // the class with the longest-running configurations first; a class without configurations ends at once
+    bool groups_done = false;
     for (int k = kClasses - 1; k >= 0; --k) {
         const ClassSpec &c = lay.cls[k];
         if (c.grid == 0) continue;                       // no configuration can fall in this class
         if (c.kind == kBiGroup) {
+            if (groups_done) continue;                   // the three group sizes share one launch
+            groups_done = true;
             BiGroupLaunch G;
             G.cfg = P.cfg; G.p_max = p_max; G.q_max = q_max; G.model = model; G.cost = cost;
             G.want_schedule = call == PRS_CALL_SCHEDULE;
-            G.times = times; G.sched = sched; G.plan = P.header; G.order = P.order; G.cls = k; G.lpc = c.lpc;
+            G.times = times; G.sched = sched; G.plan = P.header; G.order = P.order;
             G.retry = retry;
-            G.rows = reinterpret_cast<uint64_t *>(ws + c.slot_offset);
-            G.rows_per_group = c.rows_per_group;
-            G.grid = c.grid; G.stream = st;
+            for (int g = 0; g < 3; ++g) {
+                const ClassSpec &cg = lay.cls[g];
+                const bool on = cg.kind == kBiGroup && cg.grid > 0;
+                G.parts.grid[g] = on ? cg.grid : 0;
+                G.parts.rows[g] = reinterpret_cast<uint64_t *>(ws + cg.slot_offset);
+                G.parts.rows_per_group[g] = cg.rows_per_group;
+            }
+            G.stream = st;
             if (launch_bi_group(G) != hipSuccess) return PRS_EDEVICE;
         } else if (general(k, P.order, k) != hipSuccess) {
             return PRS_EDEVICE;

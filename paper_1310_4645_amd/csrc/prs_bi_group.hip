@@ -99,16 +99,15 @@ __device__ __forceinline__ void sliced_increment(uint64_t (&plane)[kPlanes], uin
 }
 
 template <typename T, bool kSched, int LPC>
-__global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
-                                                         TimesOut times, SchedOut sched, PlanHeader *plan,
-                                                         const int32_t *order, int cls, int32_t *retry,
-                                                         uint64_t *rows, size_t rows_per_group)
+__device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const ConfigArrays &cfg, int32_t p_max, int32_t q_max,
+                                              int model, const TimesOut &times, const SchedOut &sched, PlanHeader *plan,
+                                              const int32_t *order, int cls, int32_t *retry, uint64_t *rows,
+                                              size_t rows_per_group)
 {
-    PRS_DYNAMIC_LDS(lds_raw);
     constexpr int kCap = bi_group_capacity(LPC);
     const int lane = lane_id();
     const int gl = lane & (LPC - 1);                    // lane within the group = word index
-    const int group = (static_cast<int>(blockIdx.x) * kWave + lane) / LPC;
+    const int group = (block * kWave + lane) / LPC;
     // group list in LDS, entry-major so that the 64 lanes of an entry touch consecutive addresses
     constexpr int kGroups = kWave / LPC;
     const int gw = lane / LPC;                                      // configuration slot within the wavefront
@@ -377,24 +376,41 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
     }
 }
 
-template <typename T, bool kSched, int LPC>
-static void launch_one(const BiGroupLaunch &L)
+// One launch runs all three group sizes: blocks [0, g16) take the configurations with 16 lanes each (the
+// longest running, so they start first), then 4 lanes, then 1.
+template <typename T, bool kSched>
+__global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
+                                                         TimesOut times, SchedOut sched, PlanHeader *plan,
+                                                         const int32_t *order, int32_t *retry, BiGroupParts parts)
 {
-    hipLaunchKernelGGL((bi_group_kernel<T, kSched, LPC>), dim3(L.grid), dim3(kWave), bi_group_lds_bytes(LPC), L.stream, L.cfg,
-                       L.p_max, L.q_max, L.model, L.times, L.sched, L.plan, L.order, L.cls, L.retry, L.rows, L.rows_per_group);
+    PRS_DYNAMIC_LDS(lds_raw);
+    const int b = static_cast<int>(blockIdx.x);
+    if (b < parts.grid[2])
+        bi_group_body<T, kSched, 16>(lds_raw, b, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, parts.rows[2],
+                                     parts.rows_per_group[2]);
+    else if (b < parts.grid[2] + parts.grid[1])
+        bi_group_body<T, kSched, 4>(lds_raw, b - parts.grid[2], cfg, p_max, q_max, model, times, sched, plan, order, 1, retry,
+                                    parts.rows[1], parts.rows_per_group[1]);
+    else
+        bi_group_body<T, kSched, 1>(lds_raw, b - parts.grid[2] - parts.grid[1], cfg, p_max, q_max, model, times, sched, plan,
+                                    order, 0, retry, parts.rows[0], parts.rows_per_group[0]);
 }
 
-template <typename T, bool kSched> static void launch_lpc(const BiGroupLaunch &L)
+template <typename T, bool kSched> static void launch_fused(const BiGroupLaunch &L)
 {
-    if (L.lpc == 1) launch_one<T, kSched, 1>(L);
-    else if (L.lpc == 4) launch_one<T, kSched, 4>(L);
-    else launch_one<T, kSched, 16>(L);
+    size_t lds = 0;
+    for (int k = 0; k < 3; ++k)
+        if (L.parts.grid[k] > 0 && bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16)) > lds) lds = bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16));
+    const int grid = L.parts.grid[0] + L.parts.grid[1] + L.parts.grid[2];
+    hipLaunchKernelGGL((bi_group_kernel<T, kSched>), dim3(grid), dim3(kWave), lds, L.stream, L.cfg, L.p_max, L.q_max, L.model,
+                       L.times, L.sched, L.plan, L.order, L.retry, L.parts);
 }
 
 hipError_t launch_bi_group(const BiGroupLaunch &L)
 {
-    if (L.cost == PRS_COST_I64) { if (L.want_schedule) launch_lpc<int64_t, true>(L); else launch_lpc<int64_t, false>(L); }
-    else { if (L.want_schedule) launch_lpc<double, true>(L); else launch_lpc<double, false>(L); }
+    if (L.parts.grid[0] + L.parts.grid[1] + L.parts.grid[2] == 0) return hipSuccess;
+    if (L.cost == PRS_COST_I64) { if (L.want_schedule) launch_fused<int64_t, true>(L); else launch_fused<int64_t, false>(L); }
+    else { if (L.want_schedule) launch_fused<double, true>(L); else launch_fused<double, false>(L); }
     return hipGetLastError();
 }
 

@@ -48,7 +48,13 @@ size_t uni_state_bytes(bool sched, int32_t p_cap);                 // all of uni
 size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lists, per-segment counters
 size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
 size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
-// Several configurations per wavefront (p <= 1024, q <= 1023): lpc lanes per configuration.
+// Several configurations per wavefront (p <= 1024, q <= 1023): 1, 4 or 16 lanes per configuration
+// (plan classes 0, 1, 2), all three in one launch.
+struct BiGroupParts {
+    int grid[3];
+    uint64_t *rows[3];
+    size_t rows_per_group[3];
+};
 struct BiGroupLaunch {
     ConfigArrays cfg;
     int32_t p_max, q_max;
@@ -58,11 +64,8 @@ struct BiGroupLaunch {
     SchedOut sched;
     PlanHeader *plan;
     const int32_t *order;
-    int cls, lpc;
     int32_t *retry;
-    uint64_t *rows;
-    size_t rows_per_group;
-    int grid;
+    BiGroupParts parts;
     hipStream_t stream;
 };
 size_t bi_group_lds_bytes(int lpc);

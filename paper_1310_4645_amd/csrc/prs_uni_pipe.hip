@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kWave) void uni_pipe_kernel(ConfigArrays cfg, int32
                 const int pwtot = __shfl(wtot, prod, kWave), pbase = __shfl(segBase, prod, kWave),
                           pprevbase = __shfl(prevSegBase, prod, kWave);
                 const T plast = __shfl(lastS, prod, kWave), proot = __shfl(prevRoot, prod, kWave);
-                const int cfin = __shfl(fin, cons, kWave);
+                const int cfin = __shfl(fin, cons, kWave), ck = __shfl(k, cons, kWave), cia = __shfl(ia, cons, kWave);
                 // ---- how much of my input stream A is there, and a lower bound for the rest
                 int avail = 0;
                 bool complete = false;
@@ -89,30 +89,21 @@ __global__ __launch_bounds__(kWave) void uni_pipe_kernel(ConfigArrays cfg, int32
                 const bool gb0 = wb0 && wtot - (segBase + ib) > kRing - 1, gb1 = wb1 && wtot - (segBase + ib + 1) > kRing - 1;
                 if (ballot64(ga0 || ga1 || gb0 || gb1) != 0)
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // stores of earlier iterations have landed
-                if (wa0) {
-                    if (k == 0) a0 = 0;
-                    else if (ia == p - 1) a0 = proot;
-                    else if (ga0) a0 = prodbuf[static_cast<size_t>(apar) * slot_p + ia];
-                    else a0 = ring[((abase + ia) & (kRing - 1)) * kWave + prod];
-                    ha0 = true;
-                }
-                if (wa1) {
-                    if (k == 0) a1 = 0;
-                    else if (ia + 1 == p - 1) a1 = proot;
-                    else if (ga1) a1 = prodbuf[static_cast<size_t>(apar) * slot_p + ia + 1];
-                    else a1 = ring[((abase + ia + 1) & (kRing - 1)) * kWave + prod];
-                    ha1 = true;
-                }
-                if (wb0) {
-                    const T s = gb0 ? mybuf[static_cast<size_t>(par) * slot_p + ib] : ring[((segBase + ib) & (kRing - 1)) * kWave + lane];
-                    b0 = s + gg;
-                    hb0 = true;
-                }
-                if (wb1) {
-                    const T s = gb1 ? mybuf[static_cast<size_t>(par) * slot_p + ib + 1]
-                                    : ring[((segBase + ib + 1) & (kRing - 1)) * kWave + lane];
-                    b1 = s + gg;
-                    hb1 = true;
+                {
+                    // all loads first, then the selects: one wait for the slowest of them
+                    T va0 = 0, va1 = 0, vb0 = 0, vb1 = 0;
+                    if (ga0) va0 = prodbuf[static_cast<size_t>(apar) * slot_p + ia];
+                    if (ga1) va1 = prodbuf[static_cast<size_t>(apar) * slot_p + ia + 1];
+                    if (gb0) vb0 = mybuf[static_cast<size_t>(par) * slot_p + ib];
+                    if (gb1) vb1 = mybuf[static_cast<size_t>(par) * slot_p + ib + 1];
+                    const T ra0 = ring[((abase + ia) & (kRing - 1)) * kWave + prod];
+                    const T ra1 = ring[((abase + ia + 1) & (kRing - 1)) * kWave + prod];
+                    const T rb0 = ring[((segBase + ib) & (kRing - 1)) * kWave + lane];
+                    const T rb1 = ring[((segBase + ib + 1) & (kRing - 1)) * kWave + lane];
+                    if (wa0) { a0 = k == 0 ? T(0) : (ia == p - 1 ? proot : (ga0 ? va0 : ra0)); ha0 = true; }
+                    if (wa1) { a1 = k == 0 ? T(0) : (ia + 1 == p - 1 ? proot : (ga1 ? va1 : ra1)); ha1 = true; }
+                    if (wb0) { b0 = (gb0 ? vb0 : rb0) + gg; hb0 = true; }
+                    if (wb1) { b1 = (gb1 ? vb1 : rb1) + gg; hb1 = true; }
                 }
                 // ---- the two smallest remaining values, if known
                 bool ok = false;
@@ -128,6 +119,12 @@ __global__ __launch_bounds__(kWave) void uni_pipe_kernel(ConfigArrays cfg, int32
                 if (ok && !complete && !(e2 <= front)) ok = false;    // a missing value could be smaller
                 // my buffer `par` still holds the stream of two rounds ago until its reader is through with it
                 if (ns == 0 && k >= 2 * kWave && cfin < k - 2 * kWave + 1) ok = false;
+                // stay within the LDS window of my reader (it then never needs the workspace copy); with two
+                // or more values waiting the reader can always go on, so this cannot block for good
+                if (k + 1 < q) {
+                    const int consumed = ck == k + 1 ? segBase + cia : (ck < k + 1 ? prevSegBase + cia : wtot);
+                    if (wtot - consumed >= kRing - 2) ok = false;
+                }
                 if (active && ok) {
                     const T tc = e2 + cc, tr = tc + gg;              // sender leaves at tc, receiver stays until tr
                     mybuf[static_cast<size_t>(par) * slot_p + ns] = tc;
@@ -272,31 +269,41 @@ __global__ __launch_bounds__(kWave) void uni_pipe_sched_kernel(ConfigArrays cfg,
                 const bool gbi0 = wb0 && btot - (bsegBase + ib) > kRingS - 1, gbi1 = wb1 && btot - (bsegBase + ib + 1) > kRingS - 1;
                 if (ballot64(ga0 || ga1 || gbx0 || gbx1 || gbi0 || gbi1) != 0)
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-                if (wa0) {
-                    if (k == 0) { a0 = 0; a0i = ia + 1; }                 // first segment: processors 1..p-1 at time 0
-                    else if (ga0) { a0 = bufX(prod, apar)[ia]; a0i = bufI(prod, apar)[ia]; }
-                    else { const int r = ((abase + ia) & (kRingS - 1)) * kWave + prod; a0 = ringX[r]; a0i = ringI[r]; }
-                    ha0 = true;
-                }
-                if (wa1) {
-                    if (k == 0) { a1 = 0; a1i = ia + 2; }
-                    else if (ga1) { a1 = bufX(prod, apar)[ia + 1]; a1i = bufI(prod, apar)[ia + 1]; }
-                    else { const int r = ((abase + ia + 1) & (kRingS - 1)) * kWave + prod; a1 = ringX[r]; a1i = ringI[r]; }
-                    ha1 = true;
-                }
-                if (wb0) {
-                    T sx = lastS;
-                    if (ib < w) sx = gbx0 ? bufX(lane, par)[ib] : ringX[((segBase + ib) & (kRingS - 1)) * kWave + lane];
-                    b0 = sx + gg;
-                    b0i = gbi0 ? bufB[ib] : ringB[((bsegBase + ib) & (kRingS - 1)) * kWave + lane];
-                    hb0 = true;
-                }
-                if (wb1) {
-                    T sx = lastS;
-                    if (ib + 1 < w) sx = gbx1 ? bufX(lane, par)[ib + 1] : ringX[((segBase + ib + 1) & (kRingS - 1)) * kWave + lane];
-                    b1 = sx + gg;
-                    b1i = gbi1 ? bufB[ib + 1] : ringB[((bsegBase + ib + 1) & (kRingS - 1)) * kWave + lane];
-                    hb1 = true;
+                {
+                    // all loads first, then the selects: one wait for the slowest of them
+                    T va0 = 0, va1 = 0, vb0 = 0, vb1 = 0;
+                    int32_t ja0 = 0, ja1 = 0, jb0 = 0, jb1 = 0;
+                    if (ga0) { va0 = bufX(prod, apar)[ia]; ja0 = bufI(prod, apar)[ia]; }
+                    if (ga1) { va1 = bufX(prod, apar)[ia + 1]; ja1 = bufI(prod, apar)[ia + 1]; }
+                    if (gbx0) vb0 = bufX(lane, par)[ib];
+                    if (gbx1) vb1 = bufX(lane, par)[ib + 1];
+                    if (gbi0) jb0 = bufB[ib];
+                    if (gbi1) jb1 = bufB[ib + 1];
+                    const int r0 = ((abase + ia) & (kRingS - 1)) * kWave + prod, r1 = ((abase + ia + 1) & (kRingS - 1)) * kWave + prod;
+                    const T ra0 = ringX[r0], ra1 = ringX[r1];
+                    const int32_t ri0 = ringI[r0], ri1 = ringI[r1];
+                    const T rb0 = ringX[((segBase + ib) & (kRingS - 1)) * kWave + lane];
+                    const T rb1 = ringX[((segBase + ib + 1) & (kRingS - 1)) * kWave + lane];
+                    const int32_t rj0 = ringB[((bsegBase + ib) & (kRingS - 1)) * kWave + lane];
+                    const int32_t rj1 = ringB[((bsegBase + ib + 1) & (kRingS - 1)) * kWave + lane];
+                    if (wa0) {
+                        if (k == 0) { a0 = 0; a0i = ia + 1; }             // first segment: processors 1..p-1 at time 0
+                        else { a0 = ga0 ? va0 : ra0; a0i = ga0 ? ja0 : ri0; }
+                        ha0 = true;
+                    }
+                    if (wa1) {
+                        if (k == 0) { a1 = 0; a1i = ia + 2; }
+                        else { a1 = ga1 ? va1 : ra1; a1i = ga1 ? ja1 : ri1; }
+                        ha1 = true;
+                    }
+                    if (wb0) {
+                        const T sx = ib < w ? (gbx0 ? vb0 : rb0) : lastS;   // not written yet: the held entry of the running value
+                        b0 = sx + gg; b0i = gbi0 ? jb0 : rj0; hb0 = true;
+                    }
+                    if (wb1) {
+                        const T sx = ib + 1 < w ? (gbx1 ? vb1 : rb1) : lastS;
+                        b1 = sx + gg; b1i = gbi1 ? jb1 : rj1; hb1 = true;
+                    }
                 }
                 // the root of this segment: at time 0 in the first segment, else the previous segment's root
                 const bool hr = active && !rootUsed && (k == 0 || complete);
