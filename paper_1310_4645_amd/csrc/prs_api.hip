@@ -1,5 +1,8 @@
 // C ABI of the library (declared in include/prs.h): argument checks, workspace
 // carving and kernel launches.  No device memory is allocated here.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "prs_device.h"
 #include "prs_launch.h"
 
@@ -73,10 +76,11 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 //   uni-greedy, schedules:         batch kernel with state in LDS for p <= 64 / 256 / 1024, else workspace;
 //   bi-greedy:                     1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
 //                                  q <= 1023; the general kernel for the rest and for reruns.
-enum ClassKind { kUniBatch, kUniPipe, kBiGroup, kBiGeneral };
+enum ClassKind { kUniBatch, kUniPipe, kUniTimes, kBiGroup, kBiGeneral };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
+constexpr int64_t kTimesWork[kClasses - 1] = {2048, 16384, 131072};   // most pairs of a configuration run by 1, 4, 16 lanes
 constexpr int32_t kPipeMinQ = 8;       // fewer segments than this leave most lanes of the per-segment kernel idle
 
 struct ClassSpec {
@@ -114,7 +118,36 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
     L.limits.pipe_min_q = pipe ? kPipeMinQ : INT32_MAX;
     L.limits.pipe_cls = pipe ? kClasses - 2 : -1;
+    L.limits.by_work = 0;
+    for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = 0;
     static const int group_lpc[kClasses - 1] = {1, 4, 16};
+    if (model == PRS_UNI && !sched) {
+        // completion times: classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one
+        // launch, described by class 0
+        L.limits.by_work = 1;
+        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kTimesWork[k];
+        // tuning and test knob: "a,b,c" replaces the three limits (0,0,0 sends everything to the largest groups)
+        if (const char *env = getenv("PRS_UNI_GROUP_WORK")) {
+            long long a = 0, b = 0, c3 = 0;
+            if (sscanf(env, "%lld,%lld,%lld", &a, &b, &c3) == 3 && a >= 0 && b >= a && c3 >= b) {
+                L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3;
+            }
+        }
+        for (int k = 0; k < kClasses; ++k) {
+            ClassSpec &c = L.cls[k];
+            c.kind = kUniTimes; c.lpc = 0; c.rows_per_group = 0; c.lds = true; c.lds_bitmap_bytes = 0;
+            c.p_cap = (p_max + 3) / 4 * 4;
+            c.lds_bytes = uni_times_lds_bytes();
+            c.slot_bytes = k == 0 ? uni_times_slot_bytes(c.p_cap) : 0;
+            int64_t g = static_cast<int64_t>(kLdsPerCU / c.lds_bytes) * kCUs;
+            while (g > 1 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;
+            c.grid = k == 0 ? static_cast<int>(g) : 0;
+            c.slot_offset = off;
+            off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
+        }
+        L.total = off;
+        return L;
+    }
     for (int k = 0; k < kClasses; ++k) {
         ClassSpec &c = L.cls[k];
         const bool last = k == kClasses - 1;
@@ -219,6 +252,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         L.slot_p = c.p_cap; L.slot_q = q_max;
         L.grid = c.grid;
         L.stream = st;
+        if (c.kind == kUniTimes) return launch_uni_times(L);
         if (c.kind == kUniPipe) return L.want_schedule ? launch_uni_pipe_sched(L, retry) : launch_uni_pipe(L);
         return model == PRS_UNI ? launch_uni(L) : launch_bi(L);
     };

@@ -71,6 +71,9 @@ struct BiGroupLaunch {
 size_t bi_group_lds_bytes(int lpc);
 hipError_t launch_bi_group(const BiGroupLaunch &L);
 hipError_t launch_uni(const UniLaunch &L);
+size_t uni_times_lds_bytes();
+size_t uni_times_slot_bytes(int32_t p_cap);
+hipError_t launch_uni_times(const UniLaunch &L);   // all classes of a batch in one launch
 size_t uni_pipe_lds_bytes();
 size_t uni_pipe_slot_bytes(int32_t p_cap);
 hipError_t launch_uni_pipe(const UniLaunch &L);

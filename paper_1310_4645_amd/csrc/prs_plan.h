@@ -20,10 +20,18 @@ struct PlanHeader {
     int32_t cursor[kClasses * kWorkBuckets];
 };
 
-// class k holds p <= limits.p[k]; the last class the rest and every configuration with more than q segments
-// Configurations with at least pipe_min_q segments go to class pipe_cls whatever their p (disabled when
-// pipe_cls < 0).
-struct ClassLimits { int32_t p[kClasses - 1]; int32_t q; int32_t pipe_min_q; int32_t pipe_cls; };
+// By size: class k holds p <= limits.p[k]; the last class the rest and every configuration with more than q
+// segments.  Configurations with at least pipe_min_q segments go to class pipe_cls whatever their p
+// (disabled when pipe_cls < 0).
+// By work (by_work != 0): class k holds the configurations with at most work[k] pairs, the last class the rest.
+struct ClassLimits {
+    int32_t p[kClasses - 1];
+    int32_t q;
+    int32_t pipe_min_q;
+    int32_t pipe_cls;
+    int32_t by_work;
+    int64_t work[kClasses - 1];
+};
 
 struct PlanLaunch {
     ConfigArrays cfg;

@@ -8,14 +8,17 @@ __device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, i
 {
     const Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
     if (c.status != PRS_CFG_OK) return kWorkBuckets - 1;                 // nothing to do: lightest bucket of class 0
+    const int64_t work = static_cast<int64_t>(c.p - 1) * c.q;
     int cls = kClasses - 1;
-    if (lim.pipe_cls >= 0 && c.q >= lim.pipe_min_q) {
+    if (lim.by_work) {
+        for (int k = kClasses - 2; k >= 0; --k)
+            if (work <= lim.work[k]) cls = k;
+    } else if (lim.pipe_cls >= 0 && c.q >= lim.pipe_min_q) {
         cls = lim.pipe_cls;
     } else {
         for (int k = kClasses - 2; k >= 0; --k)
             if (k != lim.pipe_cls && c.p <= lim.p[k] && c.q <= lim.q) cls = k;
     }
-    const int64_t work = static_cast<int64_t>(c.p - 1) * c.q;
     int lg = 63 - __builtin_clzll(static_cast<unsigned long long>(work) | 1ULL);
     if (lg > kWorkBuckets - 1) lg = kWorkBuckets - 1;
     return cls * kWorkBuckets + (kWorkBuckets - 1 - lg);
