@@ -69,19 +69,15 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 // ---- size classes and workspace layout (shared by prs_workspace_bytes and the launches) --------------
 //
 // A batch is split into four classes, each run by the kernel and the LDS allocation that fit it:
-//   uni-greedy, completion times:  p <= 256 and p <= 1024 with few segments: batch kernel, state in LDS;
-//                                  every configuration with at least kPipeMinQ segments: one lane per
-//                                  segment; the rest (p > 1024, few segments): batch kernel, state in the
-//                                  workspace;
-//   uni-greedy, schedules:         batch kernel with state in LDS for p <= 64 / 256 / 1024, else workspace;
-//   bi-greedy:                     1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
-//                                  q <= 1023; the general kernel for the rest and for reruns.
-enum ClassKind { kUniBatch, kUniPipe, kUniTimes, kBiGroup, kBiGeneral };
+//   uni-greedy (times and schedules): by number of pairs; 1, 4, 16 or 32 lanes per configuration, all four
+//                                     classes in one launch;
+//   bi-greedy:                        1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
+//                                     q <= 1023; the general kernel for the rest and for reruns.
+enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
-constexpr int64_t kTimesWork[kClasses - 1] = {2048, 16384, 131072};   // most pairs of a configuration run by 1, 4, 16 lanes
-constexpr int32_t kPipeMinQ = 8;       // fewer segments than this leave most lanes of the per-segment kernel idle
+constexpr int64_t kUniWork[kClasses - 1] = {2048, 16384, 131072};   // most pairs of a configuration run by 1, 4, 16 lanes
 
 struct ClassSpec {
     ClassKind kind;
@@ -112,20 +108,17 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.retry = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     size_t off = L.retry + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     // which configurations go where
-    const bool pipe = model == PRS_UNI;
-    const int32_t plim_pipe[kClasses - 1] = {256, 1024, 0}, plim_std[kClasses - 1] = {64, 256, 1024};
-    for (int k = 0; k < kClasses - 1; ++k) L.limits.p[k] = pipe ? plim_pipe[k] : plim_std[k];
-    L.limits.q = model == PRS_BI ? kGroupQMax : INT32_MAX;
-    L.limits.pipe_min_q = pipe ? kPipeMinQ : INT32_MAX;
-    L.limits.pipe_cls = pipe ? kClasses - 2 : -1;
+    const int32_t plim[kClasses - 1] = {64, 256, 1024};
+    for (int k = 0; k < kClasses - 1; ++k) L.limits.p[k] = plim[k];
+    L.limits.q = kGroupQMax;
     L.limits.by_work = 0;
     for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = 0;
     static const int group_lpc[kClasses - 1] = {1, 4, 16};
-    if (model == PRS_UNI && !sched) {
-        // completion times: classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one
-        // launch, described by class 0
+    if (model == PRS_UNI) {
+        // classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one launch,
+        // described by class 0
         L.limits.by_work = 1;
-        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kTimesWork[k];
+        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kUniWork[k];
         // tuning and test knob: "a,b,c" replaces the three limits (0,0,0 sends everything to the largest groups)
         if (const char *env = getenv("PRS_UNI_GROUP_WORK")) {
             long long a = 0, b = 0, c3 = 0;
@@ -135,10 +128,10 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         }
         for (int k = 0; k < kClasses; ++k) {
             ClassSpec &c = L.cls[k];
-            c.kind = kUniTimes; c.lpc = 0; c.rows_per_group = 0; c.lds = true; c.lds_bitmap_bytes = 0;
-            c.p_cap = (p_max + 3) / 4 * 4;
-            c.lds_bytes = uni_times_lds_bytes();
-            c.slot_bytes = k == 0 ? uni_times_slot_bytes(c.p_cap) : 0;
+            c.kind = sched ? kUniSched : kUniTimes; c.lpc = 0; c.rows_per_group = 0; c.lds = true; c.lds_bitmap_bytes = 0;
+            c.p_cap = (p_max + 3) / 4 * 4;                       // keeps every per-lane array 8-byte aligned
+            c.lds_bytes = sched ? uni_sched_lds_bytes() : uni_times_lds_bytes();
+            c.slot_bytes = k != 0 ? 0 : (sched ? uni_sched_slot_bytes(c.p_cap) : uni_times_slot_bytes(c.p_cap));
             int64_t g = static_cast<int64_t>(kLdsPerCU / c.lds_bytes) * kCUs;
             while (g > 1 && static_cast<size_t>(g) * c.slot_bytes > kMaxWorkspace) g /= 2;
             c.grid = k == 0 ? static_cast<int>(g) : 0;
@@ -151,24 +144,10 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     for (int k = 0; k < kClasses; ++k) {
         ClassSpec &c = L.cls[k];
         const bool last = k == kClasses - 1;
-        const bool is_pipe = pipe && k == L.limits.pipe_cls;
-        c.p_cap = (last || is_pipe) ? p_max : (L.limits.p[k] < p_max ? L.limits.p[k] : p_max);
+        c.p_cap = last ? p_max : (L.limits.p[k] < p_max ? L.limits.p[k] : p_max);
         c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
-        bool possible = last || is_pipe || k == 0 || L.limits.p[k - 1] < p_max;   // can a configuration land here?
-        if (is_pipe) {
-            c.kind = kUniPipe;
-            c.lds = true;
-            c.p_cap = (c.p_cap + 3) / 4 * 4;                     // keeps every per-lane array 8-byte aligned
-            c.lds_bytes = sched ? uni_pipe_sched_lds_bytes() : uni_pipe_lds_bytes();
-            c.slot_bytes = sched ? uni_pipe_sched_slot_bytes(c.p_cap) : uni_pipe_slot_bytes(c.p_cap);
-            possible = q_max >= kPipeMinQ;
-        } else if (model == PRS_UNI) {
-            c.kind = kUniBatch;
-            const size_t st = uni_state_bytes(sched, c.p_cap);
-            if (!last && st <= kLdsPerBlockMax) { c.lds = true; c.lds_bytes = st; }
-            else c.slot_bytes = st;
-            if (last) possible = sched || p_max > L.limits.p[pipe ? 1 : kClasses - 2];   // schedules: also the rerun path
-        } else if (!last) {
+        const bool possible = last || k == 0 || L.limits.p[k - 1] < p_max;   // can a configuration land here?
+        if (!last) {
             // several configurations per wavefront; the slot of a wavefront holds the sent-bit rows of its groups
             c.kind = kBiGroup;
             c.lpc = group_lpc[k];
@@ -253,8 +232,8 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         L.grid = c.grid;
         L.stream = st;
         if (c.kind == kUniTimes) return launch_uni_times(L);
-        if (c.kind == kUniPipe) return L.want_schedule ? launch_uni_pipe_sched(L, retry) : launch_uni_pipe(L);
-        return model == PRS_UNI ? launch_uni(L) : launch_bi(L);
+        if (c.kind == kUniSched) return launch_uni_sched(L);
+        return launch_bi(L);
     };
     // the class with the longest-running configurations first; a class without configurations ends at once
     bool groups_done = false;
@@ -282,9 +261,8 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             return PRS_EDEVICE;
         }
     }
-    // configurations whose list of running groups did not fit go through the general kernel
-    // (bi-greedy) and schedules in which equal rounded sums upset the index order (uni-greedy) are rerun
-    if ((model == PRS_BI || call == PRS_CALL_SCHEDULE) && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
+    // bi-greedy configurations whose list of running groups did not fit go through the general kernel
+    if (model == PRS_BI && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
     return PRS_OK;
 }
 

@@ -87,6 +87,19 @@ __device__ __forceinline__ int32_t ceil_log2(int64_t v)
     return v <= 1 ? 0 : 64 - __builtin_clzll(static_cast<unsigned long long>(v - 1));
 }
 
+// sum that may take stale operands (whose result is then discarded) without signed overflow
+template <typename T> __device__ __forceinline__ T wrap_add(T a, T b);
+template <> __device__ __forceinline__ int64_t wrap_add<int64_t>(int64_t a, int64_t b)
+{
+    return static_cast<int64_t>(static_cast<uint64_t>(a) + static_cast<uint64_t>(b));
+}
+template <> __device__ __forceinline__ double wrap_add<double>(double a, double b) { return a + b; }
+
+// keeps a branch a branch (its body is then not run speculatively on the other path)
+#ifndef PRS_KEEP_BRANCH
+#define PRS_KEEP_BRANCH() asm volatile("" ::: "memory")
+#endif
+
 // ---------------------------------------------------------------- wavefront primitives
 __device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }
 

@@ -44,7 +44,6 @@ struct UniLaunch {
 
 typedef UniLaunch BiLaunch;   // same fields; slots sized by bi_slot_bytes
 
-size_t uni_state_bytes(bool sched, int32_t p_cap);                 // all of uni-greedy's state for p_cap processors
 size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lists, per-segment counters
 size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
 size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
@@ -70,16 +69,13 @@ struct BiGroupLaunch {
 };
 size_t bi_group_lds_bytes(int lpc);
 hipError_t launch_bi_group(const BiGroupLaunch &L);
-hipError_t launch_uni(const UniLaunch &L);
+// uni-greedy: all classes of a batch in one launch
 size_t uni_times_lds_bytes();
 size_t uni_times_slot_bytes(int32_t p_cap);
-hipError_t launch_uni_times(const UniLaunch &L);   // all classes of a batch in one launch
-size_t uni_pipe_lds_bytes();
-size_t uni_pipe_slot_bytes(int32_t p_cap);
-hipError_t launch_uni_pipe(const UniLaunch &L);
-size_t uni_pipe_sched_lds_bytes();
-size_t uni_pipe_sched_slot_bytes(int32_t p_cap);
-hipError_t launch_uni_pipe_sched(const UniLaunch &L, int32_t *retry);
+hipError_t launch_uni_times(const UniLaunch &L);
+size_t uni_sched_lds_bytes();
+size_t uni_sched_slot_bytes(int32_t p_cap);
+hipError_t launch_uni_sched(const UniLaunch &L);
 hipError_t launch_bi(const BiLaunch &L);
 
 struct ReplayLaunch {

@@ -1,5 +1,5 @@
-// Work plan of a batch: configurations grouped into size classes (so that each class can keep its state
-// in an LDS allocation of matching size) and, inside a class, ordered from most to least work, so the
+// Work plan of a batch: configurations grouped into classes (by size or by number of pairs, so that each
+// class gets the kernel variant and group size that fit it) and, inside a class, ordered from most to least work, so the
 // longest-running configurations start first.  Built on the device by three small kernels; no host sync.
 #pragma once
 
@@ -7,7 +7,7 @@
 
 namespace prs {
 
-constexpr int kClasses = 4;          // three LDS classes by p, one class with state in global memory
+constexpr int kClasses = 4;
 constexpr int kWorkBuckets = 40;     // floor(log2(work)) buckets, heaviest first
 constexpr int kRetryClass = kClasses; // pseudo class: configurations handed back to the general kernel
 
@@ -20,15 +20,12 @@ struct PlanHeader {
     int32_t cursor[kClasses * kWorkBuckets];
 };
 
-// By size: class k holds p <= limits.p[k]; the last class the rest and every configuration with more than q
-// segments.  Configurations with at least pipe_min_q segments go to class pipe_cls whatever their p
-// (disabled when pipe_cls < 0).
+// By size (by_work == 0): class k holds p <= limits.p[k]; the last class the rest and every configuration
+// with more than q segments.
 // By work (by_work != 0): class k holds the configurations with at most work[k] pairs, the last class the rest.
 struct ClassLimits {
     int32_t p[kClasses - 1];
     int32_t q;
-    int32_t pipe_min_q;
-    int32_t pipe_cls;
     int32_t by_work;
     int64_t work[kClasses - 1];
 };

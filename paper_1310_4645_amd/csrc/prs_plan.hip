@@ -13,11 +13,9 @@ __device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, i
     if (lim.by_work) {
         for (int k = kClasses - 2; k >= 0; --k)
             if (work <= lim.work[k]) cls = k;
-    } else if (lim.pipe_cls >= 0 && c.q >= lim.pipe_min_q) {
-        cls = lim.pipe_cls;
     } else {
         for (int k = kClasses - 2; k >= 0; --k)
-            if (k != lim.pipe_cls && c.p <= lim.p[k] && c.q <= lim.q) cls = k;
+            if (c.p <= lim.p[k] && c.q <= lim.q) cls = k;
     }
     int lg = 63 - __builtin_clzll(static_cast<unsigned long long>(work) | 1ULL);
     if (lg > kWorkBuckets - 1) lg = kWorkBuckets - 1;

@@ -1,0 +1,329 @@
+// Uni-greedy schedules (Lowery & Langou, Algorithm 1, Section 5) on gfx950: the segment pipeline of the
+// completion-time kernel with processor identities.  It emits the pairs of every segment in the order of
+// Algorithm 1 (ties by processor index, the root never sending) with their start times.
+//
+// Differences to the value-only pipeline:
+//  - stream entries are (value, sender index) and must reach the next segment sorted by both.  Senders
+//    of one start time leave with equal values and rising indices, except that the first pair of such a
+//    run may be led by a processor left over from a smaller value, and that sums of different start times
+//    can round to the same double.  The producer therefore holds back the entry with the largest index of
+//    the running value, writes the others in index order (inserting a late smaller index where it
+//    belongs), and the next segment only reads entries below the running value: they are final.
+//  - the root's final state (largest value, index 0) is a third source next to A and B: it sorts before
+//    stream entries of equal value, so it is not part of the stream (p - 1 entries per segment).
+//  - B needs the receiver's index per pair, kept in a per-lane array; its values are still S + tcomp.
+//    Equal B values are kept in index order by the same insertion.
+#include "prs_device.h"
+#include "prs_launch.h"
+
+namespace prs {
+
+constexpr int kRingS = 32;           // stream entries per lane kept in LDS
+constexpr int kNearS = kRingS - 5;   // entries this close behind the writer are read from LDS in the next iteration
+
+size_t uni_sched_lds_bytes() { return static_cast<size_t>(kRingS) * kWave * 16 + static_cast<size_t>(kWave) * 4 * 16; }
+// per lane: stream values [2][p], stream indices [2][p], receiver indices [p]
+size_t uni_sched_slot_bytes(int32_t p_cap)
+{
+    return static_cast<size_t>(kWave) * (2 * static_cast<size_t>(p_cap) * 12 + static_cast<size_t>(p_cap) * 4);
+}
+
+template <typename T> __device__ __forceinline__ bool key_less(T xa, int32_t ia, T xb, int32_t ib)
+{
+    return xa < xb || (xa == xb && ia < ib);
+}
+
+template <typename T, int G>
+__device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays &cfg, int32_t p_max, int32_t q_max,
+                                               const SchedOut &sched, PlanHeader *plan, const int32_t *order, int cls, char *slot,
+                                               int32_t slot_p)
+{
+    constexpr int M = kRingS - 1;
+    T *ringX = reinterpret_cast<T *>(lds_raw);                                   // [kRingS][64] stream values
+    int32_t *ringI = reinterpret_cast<int32_t *>(ringX + kRingS * kWave);        // [kRingS][64] stream sender indices
+    int32_t *ringB = ringI + kRingS * kWave;                                     // [kRingS][64] receiver index per pair
+    T *stT = reinterpret_cast<T *>(ringB + kRingS * kWave);                      // [64][4] start times of the lane's last pairs
+    int32_t *stS = reinterpret_cast<int32_t *>(stT + kWave * 4);                 // [64][4] their senders
+    int32_t *stD = stS + kWave * 4;                                              // [64][4] their receivers
+    const int lane = lane_id(), gl = lane & (G - 1), gbase = lane & ~(G - 1);
+    const int prod = gbase | ((gl + G - 1) & (G - 1));
+    const uint64_t gmask = (G == 64 ? ~UINT64_C(0) : ((UINT64_C(1) << G) - 1)) << gbase;
+    const size_t per_lane = 2 * static_cast<size_t>(slot_p) * 12 + static_cast<size_t>(slot_p) * 4;
+    auto bufX = [&](int l, int par) { return reinterpret_cast<T *>(slot + l * per_lane + static_cast<size_t>(par) * slot_p * 8); };
+    auto bufI = [&](int l, int par) {
+        return reinterpret_cast<int32_t *>(slot + l * per_lane + 2 * static_cast<size_t>(slot_p) * 8 + static_cast<size_t>(par) * slot_p * 4);
+    };
+    int32_t *bufB = reinterpret_cast<int32_t *>(slot + lane * per_lane + 2 * static_cast<size_t>(slot_p) * 12);
+    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    const T kInf = CostTraits<T>::inf();
+
+    // ---- per-group state (the same in all lanes of a group)
+    bool have = false, exhausted = false;
+    int64_t ci = 0, out_base = 0;
+    int p = 2, q = 1;
+    T c_full = 0, g_full = 0, c_last = 0, g_last = 0;
+    // ---- per-lane state.  Positions count stream entries (= pairs) from the start of the configuration:
+    // every finished segment adds p - 1 of them.
+    int k = 0, par = 0, apar = 0;
+    int wtot = 0, segBase = 0;      // entries written; the same at the start of my segment
+    int ns = 0;                     // pairs done in my segment (entries written + the one held back)
+    int runStart = 0;               // first entry of the running value, relative to segBase: entries before it are final
+    int apos = 0, astart = 0;       // next entry of my input stream; its first entry
+    int bpos = 0;                   // next pair of my segment whose B entry is unread (absolute)
+    bool rootUsed = false, hold = false;
+    T holdX = 0; int32_t holdI = 0; // entry of the running value held back (largest index so far)
+    T lastS = 0;                    // running value of my stream (0 before the first pair of a segment)
+    T lastBx = 0; int brun = 0;     // value of the last B entry pushed, first pair of that value (relative)
+    T prevRoot = 0, cc = 0, gg = 0;
+    bool farA = false, farB = false, anyFar = false;
+    T la0 = 0, la1 = 0, lb0 = 0, lb1 = 0;
+    int32_t lai0 = 0, lai1 = 0, lbi0 = 0, lbi1 = 0;
+
+    for (;;) {
+        // ---------------------------------------------------------------- fetch a configuration
+        if (!have && !exhausted) {
+            unsigned long long got = atomicAdd(&plan->ticket[cls], gl == 0 ? 1ULL : 0ULL);
+            int64_t ticket = static_cast<int64_t>(got);
+            if (G > 1) {
+                const uint32_t lo = __shfl(static_cast<uint32_t>(got), 0, G), hi = __shfl(static_cast<uint32_t>(got >> 32), 0, G);
+                ticket = static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+            }
+            if (ticket >= count) {
+                exhausted = true;
+            } else {
+                ci = order[begin + ticket];
+                const Config<T> c = decode_config<T>(cfg, ci, p_max, q_max);
+                int32_t status = c.status;
+                out_base = 0;
+                if (status == PRS_CFG_OK) {
+                    out_base = sched.pair_offset[ci];
+                    const int64_t n_pairs = static_cast<int64_t>(c.p - 1) * c.q;
+                    if (out_base < 0 || out_base + n_pairs > sched.pair_capacity) status = PRS_CFG_TOO_LARGE;
+                }
+                if (gl == 0) {
+                    if (sched.cfg_status) sched.cfg_status[ci] = status;
+                    if (status != PRS_CFG_OK && sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = CostTraits<T>::bad();
+                }
+                if (status == PRS_CFG_OK) {
+                    have = true;
+                    p = c.p; q = c.q;
+                    c_full = c.c_full; g_full = c.g_full; c_last = c.c_last; g_last = c.g_last;
+                    k = gl; par = 0; apar = gl == 0 ? 1 : 0;
+                    wtot = segBase = ns = runStart = apos = astart = bpos = brun = 0;
+                    rootUsed = hold = false; lastS = 0; prevRoot = 0;
+                    farA = farB = false;
+                    cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
+                }
+            }
+        }
+        if (ballot64(have) == 0 && ballot64(!exhausted) == 0) break;
+
+        const bool active = have && k < q;
+        const int n1 = p - 1;                                               // entries (pairs) per segment
+
+        // ---------------------------------------------------------------- what my producer has done so far
+        int pw = wtot, pfinal = segBase + runStart;
+        T plast = lastS, proot = prevRoot;
+        if (G > 1) {
+            pw = __shfl(wtot, prod, kWave);
+            pfinal = __shfl(segBase + runStart, prod, kWave);
+            plast = __shfl(lastS, prod, kWave);
+            proot = __shfl(prevRoot, prod, kWave);
+        }
+        const bool first = k == 0;
+        const int aend = astart + n1;
+        const int availEnd = first ? aend : (pfinal < aend ? pfinal : aend);   // entries below the producer's running value are final
+        const bool complete = first || pfinal >= aend;
+        // entries not final yet are >= the running value of a producer that is on my stream
+        const T front = complete ? kInf : (pfinal >= astart ? plast : T(0));
+
+        // ---------------------------------------------------------------- heads of A and B
+        const int r0 = (apos & M) * kWave + prod, r1 = ((apos + 1) & M) * kWave + prod;
+        T a0 = ringX[r0], a1 = ringX[r1];
+        int32_t a0i = ringI[r0], a1i = ringI[r1];
+        T sb0 = ringX[(bpos & M) * kWave + lane], sb1 = ringX[((bpos + 1) & M) * kWave + lane];
+        int32_t b0i = ringB[(bpos & M) * kWave + lane], b1i = ringB[((bpos + 1) & M) * kWave + lane];
+        if (anyFar) {                       // the same in all lanes: only this path waits for the loads at the end of the loop
+            PRS_KEEP_BRANCH();
+            if (farA) { a0 = la0; a1 = la1; a0i = lai0; a1i = lai1; }
+            if (farB) { sb0 = lb0; sb1 = lb1; b0i = lbi0; b1i = lbi1; }
+        }
+        if (first) { a0 = 0; a1 = 0; a0i = apos + 1; a1i = apos + 2; }      // first segment: processors 1..p-1 at time 0
+        const bool ha0 = apos < availEnd, ha1 = apos + 1 < availEnd;
+        // B value i is stream value i; the newest one may still be the held entry of the running value
+        if (!(bpos < wtot)) sb0 = lastS;
+        if (!(bpos + 1 < wtot)) sb1 = lastS;
+        const T b0 = wrap_add<T>(sb0, gg), b1 = wrap_add<T>(sb1, gg);
+        const bool hb0 = bpos < segBase + ns, hb1 = bpos + 1 < segBase + ns;
+        // the root of this segment: at time 0 in the first segment, else the previous segment's root
+        const bool hr = !rootUsed && complete;
+        const T rx = first ? T(0) : proot;
+
+        // ---------------------------------------------------------------- two smallest keys among A, B and the root
+        int s1 = -1, s2 = -1;                  // 0: A, 1: B, 2: root
+        T e1x = 0, e2x = 0; int32_t e1i = 0, e2i = 0;
+        {
+            T bx = 0; int32_t bi = 0;
+            if (ha0) { s1 = 0; bx = a0; bi = a0i; }
+            if (hb0 && (s1 < 0 || key_less<T>(b0, b0i, bx, bi))) { s1 = 1; bx = b0; bi = b0i; }
+            if (hr && (s1 < 0 || key_less<T>(rx, 0, bx, bi))) { s1 = 2; bx = rx; bi = 0; }
+            e1x = bx; e1i = bi;
+            // second: heads after removing the first
+            const bool ca = s1 == 0 ? ha1 : ha0, cb = s1 == 1 ? hb1 : hb0, cr = hr && s1 != 2;
+            const T ax = s1 == 0 ? a1 : a0; const int32_t ai = s1 == 0 ? a1i : a0i;
+            const T bbx = s1 == 1 ? b1 : b0; const int32_t bbi = s1 == 1 ? b1i : b0i;
+            T cx = 0; int32_t cid = 0;
+            if (ca) { s2 = 0; cx = ax; cid = ai; }
+            if (cb && (s2 < 0 || key_less<T>(bbx, bbi, cx, cid))) { s2 = 1; cx = bbx; cid = bbi; }
+            if (cr && (s2 < 0 || key_less<T>(rx, 0, cx, cid))) { s2 = 2; cx = rx; cid = 0; }
+            e2x = cx; e2i = cid;
+        }
+        // an entry that is not final yet could come first
+        const bool ok = active && s1 >= 0 && s2 >= 0 && (complete || e2x < front);
+        (void)e1x;
+
+        if (ok) {
+            const T t = e2x, tc = wrap_add<T>(t, cc), tr = wrap_add<T>(tc, gg);
+            int32_t snd = e1i, rcv = e2i;
+            if (e1i == 0) { snd = e2i; rcv = 0; }                             // the root never sends (Lemma 1 (ii))
+            // ---- the pair goes to a four-pair staging row of the lane; full rows leave as 16-byte stores
+            {
+                const int slot4 = ns & 3, row = lane * 4;
+                stS[row + slot4] = snd; stD[row + slot4] = rcv; stT[row + slot4] = t;
+                const int64_t o = out_base + static_cast<int64_t>(k) * n1 + ns;
+                if (slot4 == 3) {
+                    const int64_t o4 = o - 3;
+                    if (sched.src) __builtin_memcpy(sched.src + o4, stS + row, 16);
+                    if (sched.dst) __builtin_memcpy(sched.dst + o4, stD + row, 16);
+                    if (sched.seg) { const int32_t kk[4] = {k, k, k, k}; __builtin_memcpy(sched.seg + o4, kk, 16); }
+                    if (sched.tstart) __builtin_memcpy(static_cast<T *>(sched.tstart) + o4, stT + row, 32);
+                } else if (ns == n1 - 1) {                                    // the segment ends inside a row
+                    for (int j = 0; j <= slot4; ++j) {
+                        const int64_t oj = o - slot4 + j;
+                        if (sched.src) sched.src[oj] = stS[row + j];
+                        if (sched.dst) sched.dst[oj] = stD[row + j];
+                        if (sched.seg) sched.seg[oj] = k;
+                        if (sched.tstart) static_cast<T *>(sched.tstart)[oj] = stT[row + j];
+                    }
+                }
+            }
+            T *const myX = bufX(lane, par);
+            int32_t *const myI = bufI(lane, par);
+            int w = wtot - segBase;                                           // entries written in this segment
+            // ---- stream entry (tc, snd): keep the largest index of the running value back
+            T wx = 0; int32_t wi = 0; bool wr = false;
+            if (hold && tc == holdX) {
+                if (snd > holdI) { wx = holdX; wi = holdI; holdI = snd; } else { wx = tc; wi = snd; }
+                wr = true;
+            } else {
+                if (hold) { wx = holdX; wi = holdI; wr = true; }
+                hold = true; holdX = tc; holdI = snd;
+            }
+            if (wr) {
+                // entries of the running value are written in rising index order; a smaller index that comes
+                // late is inserted (the next segment does not read the running value yet)
+                int at = w;
+                while (at > runStart && myI[at - 1] > wi) {
+                    const int32_t mv = myI[at - 1];
+                    myI[at] = mv;
+                    if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
+                    --at;
+                }
+                myX[w] = wx; myI[at] = wi;
+                ringX[(wtot & M) * kWave + lane] = wx;
+                if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = wi;
+                ++w; ++wtot;
+            }
+            if (!(tc == lastS) || ns == 0) runStart = w;                      // entries before the running value are final
+            lastS = tc;
+            // ---- B entry (tr, rcv) of pair ns; equal values keep rising index order
+            if (ns == 0 || !(tr == lastBx)) brun = ns;
+            lastBx = tr;
+            {
+                int at = ns;
+                const int ib = bpos - segBase;
+                const int lo = brun > ib ? brun : ib;
+                while (at > lo && bufB[at - 1] > rcv) {
+                    const int32_t mv = bufB[at - 1];
+                    bufB[at] = mv;
+                    if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = mv;
+                    --at;
+                }
+                bufB[at] = rcv;
+                if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = rcv;
+            }
+            // ---- consume
+            if (s1 == 2 || s2 == 2) rootUsed = true;
+            const int dA = (s1 == 0 ? 1 : 0) + (s2 == 0 ? 1 : 0), dB = (s1 == 1 ? 1 : 0) + (s2 == 1 ? 1 : 0);
+            apos += dA; bpos += dB;
+            ++ns;
+            if (ns == n1) {                                                   // segment done: flush, hand over
+                myX[w] = holdX; myI[w] = holdI;                               // the held index is the largest of its value
+                ringX[(wtot & M) * kWave + lane] = holdX; ringI[(wtot & M) * kWave + lane] = holdI;
+                ++wtot;
+                hold = false;
+                prevRoot = tr;
+                if (k == q - 1 && sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = tr;
+                k += G; par ^= 1;
+                segBase = wtot; ns = 0; runStart = 0; brun = 0; bpos = wtot;
+                rootUsed = false; lastS = 0;
+                astart = gl == 0 ? segBase - n1 : segBase;                    // the stream my producer writes in its current round
+                apar = gl == 0 ? par ^ 1 : par;
+                apos = astart;
+                cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
+            }
+        }
+        const bool on = have && k < q;
+        const uint64_t on_mask = ballot64(on);
+        if ((on_mask & gmask) == 0) have = false;                            // every lane of the group is through: fetch next
+
+        // ---------------------------------------------------------------- entries too far back for LDS: load them now
+        farA = on && k > 0 && pw - apos > kNearS;
+        farB = on && segBase + ns - bpos > kNearS;
+        anyFar = ballot64(farA || farB) != 0;
+        if (anyFar) {
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+            if (farA) {
+                const int i0 = apos - astart < n1 ? apos - astart : n1 - 1, i1 = i0 + 1 < n1 ? i0 + 1 : n1 - 1;
+                la0 = bufX(prod, apar)[i0]; lai0 = bufI(prod, apar)[i0];
+                la1 = bufX(prod, apar)[i1]; lai1 = bufI(prod, apar)[i1];
+            }
+            if (farB) {
+                const int i0 = bpos - segBase;                                // far: both entries were written long ago
+                lb0 = bufX(lane, par)[i0]; lbi0 = bufB[i0];
+                lb1 = bufX(lane, par)[i0 + 1]; lbi1 = bufB[i0 + 1];
+            }
+        }
+    }
+}
+
+// One launch for the whole batch: every wavefront works through the classes from the heaviest
+// configurations (largest groups) to the lightest.
+template <typename T>
+__global__ __launch_bounds__(kWave) void uni_sched_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, SchedOut sched,
+                                                          PlanHeader *plan, const int32_t *order, char *slots, size_t slot_bytes,
+                                                          int32_t slot_p)
+{
+    PRS_DYNAMIC_LDS(lds_raw);
+    char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
+    uni_sched_body<T, 32>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, slot, slot_p);
+    __syncthreads();
+    uni_sched_body<T, 16>(lds_raw, cfg, p_max, q_max, sched, plan, order, 2, slot, slot_p);
+    __syncthreads();
+    uni_sched_body<T, 4>(lds_raw, cfg, p_max, q_max, sched, plan, order, 1, slot, slot_p);
+    __syncthreads();
+    uni_sched_body<T, 1>(lds_raw, cfg, p_max, q_max, sched, plan, order, 0, slot, slot_p);
+}
+
+hipError_t launch_uni_sched(const UniLaunch &L)
+{
+    if (L.cost == PRS_COST_I64)
+        hipLaunchKernelGGL((uni_sched_kernel<int64_t>), dim3(L.grid), dim3(kWave), uni_sched_lds_bytes(), L.stream, L.cfg, L.p_max,
+                           L.q_max, L.sched, L.plan, L.order, L.slots, L.slot_bytes, L.slot_p);
+    else
+        hipLaunchKernelGGL((uni_sched_kernel<double>), dim3(L.grid), dim3(kWave), uni_sched_lds_bytes(), L.stream, L.cfg, L.p_max,
+                           L.q_max, L.sched, L.plan, L.order, L.slots, L.slot_bytes, L.slot_p);
+    return hipGetLastError();
+}
+
+}  // namespace prs

@@ -31,23 +31,11 @@
 
 namespace prs {
 
-constexpr int kRing = 32;          // stream entries per lane kept in LDS
+constexpr int kRing = 64;          // stream entries per lane kept in LDS
 constexpr int kNear = kRing - 5;   // entries this close behind the writer are read from LDS in the next iteration
 
 size_t uni_times_lds_bytes() { return static_cast<size_t>(kRing) * kWave * 8; }
 size_t uni_times_slot_bytes(int32_t p_cap) { return static_cast<size_t>(kWave) * 2 * static_cast<size_t>(p_cap) * 8; }
-
-// keeps a branch a branch (its body is then not run speculatively on the other path)
-#ifndef PRS_KEEP_BRANCH
-#define PRS_KEEP_BRANCH() asm volatile("" ::: "memory")
-#endif
-
-template <typename T> __device__ __forceinline__ T wrap_add(T a, T b);
-template <> __device__ __forceinline__ int64_t wrap_add<int64_t>(int64_t a, int64_t b)
-{
-    return static_cast<int64_t>(static_cast<uint64_t>(a) + static_cast<uint64_t>(b));   // stale ring entries may be anything
-}
-template <> __device__ __forceinline__ double wrap_add<double>(double a, double b) { return a + b; }
 
 template <typename T, int G>
 __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg, int32_t p_max, int32_t q_max, int model,

@@ -121,6 +121,33 @@ def test_integer_costs_ragged_segments_and_larger_p(prs, model):
     _check_schedules(prs, host, model, 256, 32)
 
 
+@pytest.mark.parametrize("limits", ["0,0,0", "0,0,1000000000", "0,1000000000,1000000000", "1000000000,1000000000,1000000000"])
+def test_uni_every_group_size(prs, limits, monkeypatch):
+    """Uni-greedy runs a configuration on 32, 16, 4 or 1 lanes depending on its number of pairs; here every
+    group size gets the same mixed batch (integer and fp64 costs, with fp64 rounding collisions)."""
+    monkeypatch.setenv("PRS_UNI_GROUP_WORK", limits)
+    rng = np.random.default_rng(77)
+    n = 96
+    p = rng.integers(2, 160, n).astype(np.int32)
+    p[:8] = [2, 3, 31, 32, 33, 64, 65, 129]
+    q = rng.integers(1, 80, n).astype(np.int32)
+    q[:8] = [1, 70, 1, 33, 65, 31, 32, 5]
+    m = (q.astype(np.int64) * rng.integers(1, 4, n) + rng.integers(0, 2, n)).astype(np.int64)
+    host = prs_inputs.SweepConfigs(p, q, m, rng.integers(1, 12, n).astype(np.int64), rng.integers(0, 4, n).astype(np.int64),
+                                   rng.integers(0, 4, n).astype(np.int64), "i64")
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, 0, 160, 80)
+    _sync()
+    _check_times(got, O.simulate_batch(host, 0), exact=True)
+    _check_schedules(prs, host, 0, 160, 80)
+    hostf = prs_inputs.SweepConfigs(p[:40], q[:40], m[:40], np.full(40, 1.0), np.full(40, 0.0), np.full(40, 2.0 ** -52), "f64")
+    devf = prs.DeviceConfigs.from_host(hostf)
+    gotf = prs.simulate_completion_batch(devf, 0, 160, 80)
+    _sync()
+    assert np.array_equal(_np(gotf["greedy"]), O.simulate_batch(hostf, 0).T_greedy)
+    _check_schedules(prs, hostf, 0, 160, 80)
+
+
 # --------------------------------------------------------------------------- fp64 sweeps
 def _fast_subset(host, budget, limit):
     """indices of configurations the plain oracle finishes quickly (cost ~ p^2 q)."""
