@@ -219,20 +219,35 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 if (hold) { wx = holdX; wi = holdI; wr = true; }
                 hold = true; holdX = tc; holdI = snd;
             }
+            // Entries reach the workspace in rows of four (16-byte stores) once a row is complete; younger
+            // ones are in LDS only.  What is read from the workspace is always more than a row old.
             if (wr) {
                 // entries of the running value are written in rising index order; a smaller index that comes
                 // late is inserted (the next segment does not read the running value yet)
+                const int rows_done = w & ~3;
                 int at = w;
-                while (at > runStart && myI[at - 1] > wi) {
-                    const int32_t mv = myI[at - 1];
-                    myI[at] = mv;
+                for (;;) {
+                    if (at <= runStart) break;
+                    const int32_t mv = w + 1 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
+                    if (!(mv > wi)) break;
                     if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
+                    if (at < rows_done) myI[at] = mv;
                     --at;
                 }
-                myX[w] = wx; myI[at] = wi;
                 ringX[(wtot & M) * kWave + lane] = wx;
                 if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = wi;
+                if (at < rows_done) myI[at] = wi;
                 ++w; ++wtot;
+                if ((w & 3) == 0) {
+                    T rx4[4]; int32_t ri4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int rr = ((segBase + w - 4 + j) & M) * kWave + lane;
+                        rx4[j] = ringX[rr]; ri4[j] = ringI[rr];
+                    }
+                    __builtin_memcpy(myX + w - 4, rx4, 32);
+                    __builtin_memcpy(myI + w - 4, ri4, 16);
+                }
             }
             if (!(tc == lastS) || ns == 0) runStart = w;                      // entries before the running value are final
             lastS = tc;
@@ -240,17 +255,26 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             if (ns == 0 || !(tr == lastBx)) brun = ns;
             lastBx = tr;
             {
+                const int rows_done = ns & ~3;
                 int at = ns;
                 const int ib = bpos - segBase;
                 const int lo = brun > ib ? brun : ib;
-                while (at > lo && bufB[at - 1] > rcv) {
-                    const int32_t mv = bufB[at - 1];
-                    bufB[at] = mv;
+                for (;;) {
+                    if (at <= lo) break;
+                    const int32_t mv = ns + 1 - at <= kRingS ? ringB[((segBase + at - 1) & M) * kWave + lane] : bufB[at - 1];
+                    if (!(mv > rcv)) break;
                     if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = mv;
+                    if (at < rows_done) bufB[at] = mv;
                     --at;
                 }
-                bufB[at] = rcv;
                 if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = rcv;
+                if (at < rows_done) bufB[at] = rcv;
+                if (((ns + 1) & 3) == 0) {
+                    int32_t rb4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) rb4[j] = ringB[((segBase + ns - 3 + j) & M) * kWave + lane];
+                    __builtin_memcpy(bufB + ns - 3, rb4, 16);
+                }
             }
             // ---- consume
             if (s1 == 2 || s2 == 2) rootUsed = true;
@@ -258,9 +282,14 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             apos += dA; bpos += dB;
             ++ns;
             if (ns == n1) {                                                   // segment done: flush, hand over
-                myX[w] = holdX; myI[w] = holdI;                               // the held index is the largest of its value
+                // the held index is the largest of its value: it is the last entry (w = n1 - 1)
                 ringX[(wtot & M) * kWave + lane] = holdX; ringI[(wtot & M) * kWave + lane] = holdI;
                 ++wtot;
+                for (int j = w & ~3; j <= w; ++j) {                           // the last row, complete or not
+                    const int rr = ((segBase + j) & M) * kWave + lane;
+                    myX[j] = ringX[rr]; myI[j] = ringI[rr];
+                    bufB[j] = ringB[rr];
+                }
                 hold = false;
                 prevRoot = tr;
                 if (k == q - 1 && sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = tr;
