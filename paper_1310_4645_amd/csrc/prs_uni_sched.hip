@@ -223,12 +223,13 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             // ones are in LDS only.  What is read from the workspace is always more than a row old.
             if (wr) {
                 // entries of the running value are written in rising index order; a smaller index that comes
-                // late is inserted (the next segment does not read the running value yet)
+                // late is inserted (the next segment does not read the running value yet).  The new entry takes
+                // over the LDS slot of the one kRingS places back, so that one is read from the workspace.
                 const int rows_done = w & ~3;
                 int at = w;
                 for (;;) {
                     if (at <= runStart) break;
-                    const int32_t mv = w + 1 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
+                    const int32_t mv = w + 2 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
                     if (!(mv > wi)) break;
                     if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
                     if (at < rows_done) myI[at] = mv;
@@ -261,7 +262,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 const int lo = brun > ib ? brun : ib;
                 for (;;) {
                     if (at <= lo) break;
-                    const int32_t mv = ns + 1 - at <= kRingS ? ringB[((segBase + at - 1) & M) * kWave + lane] : bufB[at - 1];
+                    const int32_t mv = ns + 2 - at <= kRingS ? ringB[((segBase + at - 1) & M) * kWave + lane] : bufB[at - 1];
                     if (!(mv > rcv)) break;
                     if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = mv;
                     if (at < rows_done) bufB[at] = mv;

@@ -178,6 +178,15 @@ def test_fp64_sweep_sample_schedules(prs, model):
     _check_schedules(prs, full.take(idx), model, 1024, 512)
 
 
+def test_uni_schedules_with_long_runs_of_equal_values(prs):
+    """Several hundred processors: the first segments send in runs of hundreds of equal values, B grows past
+    what the kernel keeps in LDS, and late small indices are inserted far back (also exactly one LDS ring back)."""
+    full = prs_inputs.uni_sweep(3000)
+    work = full.p.astype(np.float64) ** 2 * full.q_req
+    idx = np.nonzero((full.p >= 300) & (work <= 4e7))[0][:40]
+    _check_schedules(prs, full.take(idx), 0, 1024, 512)
+
+
 @pytest.mark.parametrize("model", [0, 1])
 def test_fp64_rounding_ties(prs, model):
     # costs chosen so that sums produced at different times round to the same double
