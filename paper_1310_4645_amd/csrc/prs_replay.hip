@@ -22,16 +22,16 @@
 
 namespace prs {
 
-constexpr int kReplayThreads = 256;
+constexpr int kReplayThreads = 128;
 constexpr int kBuildThreads = 256;
 constexpr int kStackDepth = 24;      // saved partial sums per element
-constexpr int kPrefetch = 8;         // loads in flight per lane
+constexpr int kPrefetch = 8;         // rows per group of loads; two groups are in flight per lane
 
 struct ReplayWs {
     int64_t *offsets;      // q+1
     uint32_t *prog;        // q*p
     int32_t *tmp;          // q * 8 * p scratch of the builder
-    int32_t *flags;        // [0] invalid, [1] too deep
+    int32_t *flags;        // [0] invalid, [1] too deep, [2] saved partial sums needed at once
 };
 
 __host__ __device__ inline size_t rp_align(size_t v) { return (v + 255) / 256 * 256; }
@@ -53,7 +53,7 @@ static ReplayWs carve_replay(char *ws, int32_t p, int32_t q)
     return w;
 }
 
-__global__ void replay_clear_flags(int32_t *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
+__global__ void replay_clear_flags(int32_t *flags) { if (threadIdx.x < 3) flags[threadIdx.x] = 0; }
 
 // Segment offsets travel as kernel arguments, a chunk at a time: no host-to-device copy is enqueued.
 constexpr int kOffsetChunk = 256;
@@ -151,6 +151,7 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
                                                  (static_cast<uint32_t>(npop) << 21);
     }
     if (deepest + 1 > kStackDepth) flags[1] = 1;
+    atomicMax(&flags[2], deepest + 1);
 }
 
 template <typename E> struct Vec4 { E v[4]; };
@@ -187,66 +188,104 @@ __device__ __forceinline__ Acc<E, VEC> load_elems(const E *ptr, int nvalid)
     return a;
 }
 
-// stack of saved partial sums in registers; sp is uniform over the wavefront
-#define PRS_STACK_CASES(OP) \
-    OP(0) OP(1) OP(2) OP(3) OP(4) OP(5) OP(6) OP(7) OP(8) OP(9) OP(10) OP(11) OP(12) OP(13) OP(14) OP(15) \
-    OP(16) OP(17) OP(18) OP(19) OP(20) OP(21) OP(22) OP(23)
-
 template <typename E, int VEC>
-__global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const int64_t *offsets, const uint32_t *prog,
-                                                                const E *in, int64_t stride, E *out, const int32_t *flags)
+__device__ __forceinline__ void store_elems(E *ptr, const Acc<E, VEC> &a, int nvalid)
 {
-    if (flags[0] | flags[1]) return;
-    const int k = blockIdx.y;
-    const int64_t lo = offsets[k], hi = offsets[k + 1];
-    const int64_t e0 = lo + (static_cast<int64_t>(blockIdx.x) * kReplayThreads + threadIdx.x) * VEC;
-    if (e0 >= hi) return;
-    const int nvalid = hi - e0 >= VEC ? VEC : static_cast<int>(hi - e0);
-    const uint32_t *pg = prog + static_cast<size_t>(k) * p;
-    Acc<E, VEC> acc;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc.v[i] = E(0);
-    Acc<E, VEC> stk[kStackDepth];
-    int sp = 0;
-    for (int base = 0; base < p; base += kPrefetch) {
-        uint32_t ent[kPrefetch];
-        Acc<E, VEC> val[kPrefetch];
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) ent[u] = base + u < p ? pg[base + u] : 0u;
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u)
-            if (base + u < p) val[u] = load_elems<E, VEC>(in + static_cast<int64_t>(ent[u] & 0xFFFFFu) * stride + e0, nvalid);
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) {
-            if (base + u >= p) break;
-            if ((ent[u] >> 20) & 1u) {
-#define PRS_PUSH(d) case d: stk[d] = acc; break;
-                switch (sp) { PRS_STACK_CASES(PRS_PUSH) default: break; }
-#undef PRS_PUSH
-                ++sp;
-                acc = val[u];
-            } else {
-                acc.add(val[u]);
-            }
-            for (int np = static_cast<int>(ent[u] >> 21); np > 0; --np) {
-                --sp;
-                Acc<E, VEC> top;
-#define PRS_POP(d) case d: top = stk[d]; break;
-                switch (sp) { PRS_STACK_CASES(PRS_POP) default: top = acc; break; }
-#undef PRS_POP
-                top.add(acc);            // saved partial sum + finished subtree
-                acc = top;
-            }
-        }
-    }
     if (VEC == 4 && nvalid == 4) {
         float4 f;
         E *fe = reinterpret_cast<E *>(&f);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) fe[i] = acc.v[i];
-        *reinterpret_cast<float4 *>(out + e0) = f;
+        for (int i = 0; i < VEC; ++i) fe[i] = a.v[i];
+        *reinterpret_cast<float4 *>(ptr) = f;
     } else {
-        for (int i = 0; i < nvalid; ++i) out[e0 + i] = acc.v[i];
+        for (int i = 0; i < nvalid; ++i) ptr[i] = a.v[i];
+    }
+}
+
+// One thread reduces VEC neighbouring elements of a segment by running the segment's program: p entries
+// (row | push << 20 | pops << 21), the same for every thread of a block.  The partial sums a push saves sit
+// in LDS ([depth][thread], 16 bytes per thread and level), so the registers are free for the loads: two
+// groups of kPrefetch rows are in flight while the group before them is added up.  The LDS allocation fixes
+// the depth D (8, 16 or 24 levels, the fewer the more blocks fit on a CU); every variant is launched and only
+// the one that fits the schedule's trees (flags[2], found by replay_build) runs.
+template <typename E, int VEC>
+__device__ __forceinline__ void replay_step(Acc<E, VEC> &acc, int &sp, E *stk, uint32_t ent, const Acc<E, VEC> &val)
+{
+    if ((ent >> 20) & 1u) {
+        E *slot = stk + static_cast<size_t>(sp) * kReplayThreads * VEC;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) slot[i] = acc.v[i];
+        ++sp;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc.v[i] = val.v[i];
+    } else {
+        acc.add(val);
+    }
+    for (int np = static_cast<int>(ent >> 21); np > 0; --np) {
+        --sp;
+        const E *slot = stk + static_cast<size_t>(sp) * kReplayThreads * VEC;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc.v[i] = add1<E>(slot[i], acc.v[i]);   // saved partial sum + finished subtree
+    }
+}
+
+template <typename E, int VEC, int D>
+__global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const int64_t *__restrict__ offsets,
+                                                                const uint32_t *__restrict__ prog, const E *__restrict__ in,
+                                                                int64_t stride, E *__restrict__ out,
+                                                                const int32_t *__restrict__ flags)
+{
+    PRS_DYNAMIC_LDS(lds_raw);
+    if (flags[0] | flags[1]) return;
+    const int need = flags[2];
+    if (need > D || need <= D - 8) return;                     // another depth variant takes this schedule
+    const int k = blockIdx.y;
+    const int64_t lo = offsets[k], hi = offsets[k + 1];
+    const int64_t b0 = lo + static_cast<int64_t>(blockIdx.x) * kReplayThreads * VEC;
+    if (b0 >= hi) return;
+    const int64_t e0 = b0 + static_cast<int64_t>(threadIdx.x) * VEC;
+    const uint32_t *pg = prog + static_cast<size_t>(k) * p;
+    Acc<E, VEC> acc;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc.v[i] = E(0);
+    E *const stk = reinterpret_cast<E *>(lds_raw) + static_cast<size_t>(threadIdx.x) * VEC;   // this thread's column of the LDS stack
+    int sp = 0;
+    const bool full = b0 + static_cast<int64_t>(kReplayThreads) * VEC <= hi;   // every thread of the block has VEC elements
+    if (full) {
+        // entries past the end of the program repeat the last row (loaded, not used): the loads stay
+        // unconditional, so that waiting for one group does not wait for the next
+        auto row = [&](int idx) { return pg[idx < p ? idx : p - 1]; };
+        uint32_t entA[kPrefetch], entB[kPrefetch];
+        Acc<E, VEC> valA[kPrefetch], valB[kPrefetch];
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) entA[u] = row(u);
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) valA[u] = load_elems<E, VEC>(in + static_cast<int64_t>(entA[u] & 0xFFFFFu) * stride + e0, VEC);
+        for (int base = 0; base < p; base += 2 * kPrefetch) {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) entB[u] = row(base + kPrefetch + u);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) valB[u] = load_elems<E, VEC>(in + static_cast<int64_t>(entB[u] & 0xFFFFFu) * stride + e0, VEC);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u)
+                if (base + u < p) replay_step<E, VEC>(acc, sp, stk, entA[u], valA[u]);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) entA[u] = row(base + 2 * kPrefetch + u);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) valA[u] = load_elems<E, VEC>(in + static_cast<int64_t>(entA[u] & 0xFFFFFu) * stride + e0, VEC);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u)
+                if (base + kPrefetch + u < p) replay_step<E, VEC>(acc, sp, stk, entB[u], valB[u]);
+        }
+        store_elems<E, VEC>(out + e0, acc, VEC);
+    } else if (e0 < hi) {
+        // ragged end of a segment: plain loop
+        const int nvalid = hi - e0 >= VEC ? VEC : static_cast<int>(hi - e0);
+        for (int idx = 0; idx < p; ++idx) {
+            const uint32_t ent = pg[idx];
+            replay_step<E, VEC>(acc, sp, stk, ent, load_elems<E, VEC>(in + static_cast<int64_t>(ent & 0xFFFFFu) * stride + e0, nvalid));
+        }
+        store_elems<E, VEC>(out + e0, acc, nvalid);
     }
 }
 
@@ -254,6 +293,8 @@ __global__ void replay_write_status(const int32_t *flags, int32_t *status)
 {
     if (threadIdx.x == 0 && status) *status = flags[0] ? 1 : (flags[1] ? 2 : 0);
 }
+
+static size_t replay_lds_bytes(int vec, int depth) { return static_cast<size_t>(depth) * kReplayThreads * vec * 4; }
 
 template <typename E>
 static hipError_t launch_replay_t(const ReplayLaunch &L, const ReplayWs &w, int64_t max_len, bool vec_ok)
@@ -264,11 +305,19 @@ static hipError_t launch_replay_t(const ReplayLaunch &L, const ReplayWs &w, int6
         if (vec_ok) {
             const int64_t groups = (max_len + 3) / 4;
             dim3 grid(static_cast<unsigned>((groups + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
-            hipLaunchKernelGGL((replay_kernel<E, 4>), grid, dim3(kReplayThreads), 0, L.stream, L.p, w.offsets, w.prog, in,
+            hipLaunchKernelGGL((replay_kernel<E, 4, 8>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 8), L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+            hipLaunchKernelGGL((replay_kernel<E, 4, 16>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 16), L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+            hipLaunchKernelGGL((replay_kernel<E, 4, 24>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 24), L.stream, L.p, w.offsets, w.prog, in,
                                L.stride_elems, out, w.flags);
         } else {
             dim3 grid(static_cast<unsigned>((max_len + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
-            hipLaunchKernelGGL((replay_kernel<E, 1>), grid, dim3(kReplayThreads), 0, L.stream, L.p, w.offsets, w.prog, in,
+            hipLaunchKernelGGL((replay_kernel<E, 1, 8>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 8), L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+            hipLaunchKernelGGL((replay_kernel<E, 1, 16>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 16), L.stream, L.p, w.offsets, w.prog, in,
+                               L.stride_elems, out, w.flags);
+            hipLaunchKernelGGL((replay_kernel<E, 1, 24>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 24), L.stream, L.p, w.offsets, w.prog, in,
                                L.stride_elems, out, w.flags);
         }
     }
