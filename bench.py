@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of 1 GiB (calibrates the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the sweep is a batch of independent configurations and nothing here "
@@ -144,6 +146,12 @@ def main():
         prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_f, out=out_f, workspace=rws)
         mark(6)
 
+    if args.copy_probe:
+        a = torch.empty(2 ** 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
