@@ -61,6 +61,11 @@ def cpu_baseline(host, seconds_hint=20.0):
                       f"completion times with baselines, {dt:.1f} s of wall time"}
 
 
+# per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
+PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 6.1e8, "schedule_uni": 4.97e10, "schedule_bi": 2.48e10,
+                          "replay_i32": 4.33e9, "replay_f32": 4.33e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,7 +184,9 @@ def main():
         roof = {"bound": "alu", "achieved": ops / (part_ms[dominant] * 1e-3) / 1e12, "peak": PEAK_FP64_OPS / 1e12,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    # HBM bytes per launch of that call's kernel, from the rocprofv3 counter runs summarised under profiles/
+    # (FETCH_SIZE and WRITE_SIZE, scaled by what they read for a 1 GiB copy); None where not collected
+    roof["traffic"] = PROFILED_TRAFFIC_BYTES.get(dominant)
     roof["kernel"] = dominant
     replay_bytes = 4.0 * REPLAY_N * (REPLAY_P + 1)
     out = {
@@ -198,7 +205,10 @@ def main():
                         "bi_schedule": n_pairs / (part_ms["schedule_bi"] * 1e-3)},
         "replay": {"i32_GBps": replay_bytes / (part_ms["replay_i32"] * 1e-3) / 1e9,
                    "f32_GBps": replay_bytes / (part_ms["replay_f32"] * 1e-3) / 1e9,
-                   "peak_GBps": PEAK_HBM / 1e9, "algorithmic_bytes": replay_bytes},
+                   "peak_GBps": PEAK_HBM / 1e9, "algorithmic_bytes": replay_bytes,
+                   "frac_of_peak": replay_bytes / (min(part_ms["replay_i32"], part_ms["replay_f32"]) * 1e-3) / PEAK_HBM,
+                   "traffic": PROFILED_TRAFFIC_BYTES["replay_f32"],
+                   "note": "whole replay_reduction call (schedule check and program build included)"},
         "schedule_emission_GBps": {"uni": n_pairs * 20.0 / (part_ms["schedule_uni"] * 1e-3) / 1e9,
                                    "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
         "roofline": roof,
