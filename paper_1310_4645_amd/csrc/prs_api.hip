@@ -95,6 +95,7 @@ struct Layout {
     size_t header, order, retry, total;
     ClassLimits limits;
     ClassSpec cls[kClasses];
+    bool bi_on[kClasses - 1];     // bi-greedy group classes a configuration can fall into
 };
 
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
@@ -180,6 +181,18 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         if (g > n) g = n < 1 ? 1 : n;
         if (!possible) g = 0;
         c.grid = static_cast<int>(g);
+        if (!last) L.bi_on[k] = possible;
+    }
+    // the group classes share one resident set of blocks, carried by class 0: as many as the largest LDS
+    // allocation of a usable class allows (their slots of sent-bit rows have the same size)
+    {
+        int g = 0;
+        for (int k = 0; k < kClasses - 1; ++k)
+            if (L.bi_on[k] && (g == 0 || L.cls[k].grid < g)) g = L.cls[k].grid;
+        for (int k = 0; k < kClasses - 1; ++k) L.cls[k].grid = k == 0 ? g : 0;
+    }
+    for (int k = 0; k < kClasses; ++k) {
+        ClassSpec &c = L.cls[k];
         c.slot_offset = off;
         off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
     }
@@ -248,13 +261,25 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             G.want_schedule = call == PRS_CALL_SCHEDULE;
             G.times = times; G.sched = sched; G.plan = P.header; G.order = P.order;
             G.retry = retry;
+            // one resident set of blocks (class 0 carries its size and the sent-bit rows), split between the
+            // classes the blocks start with
+            const ClassSpec &c0 = lay.cls[0];
+            int total = c0.grid, enabled = 0;
+            static const int share[3] = {2, 3, 5};                         // tenths of the blocks that start with class 0, 1, 2
             for (int g = 0; g < 3; ++g) {
-                const ClassSpec &cg = lay.cls[g];
-                const bool on = cg.kind == kBiGroup && cg.grid > 0;
-                G.parts.grid[g] = on ? cg.grid : 0;
-                G.parts.rows[g] = reinterpret_cast<uint64_t *>(ws + cg.slot_offset);
-                G.parts.rows_per_group[g] = cg.rows_per_group;
+                G.parts.on[g] = lay.cls[g].kind == kBiGroup && lay.cls[g].lpc > 0 && lay.cls[g].rows_per_group > 0 && lay.bi_on[g];
+                G.parts.rows_per_group[g] = lay.cls[g].rows_per_group;
+                if (G.parts.on[g]) enabled += share[g];
             }
+            int given = 0;
+            for (int g = 2; g >= 0; --g) {
+                G.parts.start[g] = G.parts.on[g] ? total * share[g] / enabled : 0;
+                given += G.parts.start[g];
+            }
+            for (int g = 2; g >= 0; --g)
+                if (G.parts.on[g]) { G.parts.start[g] += total - given; break; }   // rounding remainder
+            G.parts.rows = reinterpret_cast<uint64_t *>(ws + c0.slot_offset);
+            G.parts.rows_per_block = c0.slot_bytes / 8;
             G.stream = st;
             if (launch_bi_group(G) != hipSuccess) return PRS_EDEVICE;
         } else if (general(k, P.order, k) != hipSuccess) {

@@ -376,8 +376,10 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     }
 }
 
-// One launch runs all three group sizes: blocks [0, g16) take the configurations with 16 lanes each (the
-// longest running, so they start first), then 4 lanes, then 1.
+// One launch runs all three group sizes on one resident set of blocks.  The first start[2] blocks begin with
+// the 16-lane configurations, the next start[1] with the 4-lane ones, the rest with the 1-lane ones, so the
+// longest-running configurations of every class start at once; a block whose class has run out of tickets
+// goes on with the others (largest groups first).
 template <typename T, bool kSched>
 __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
                                                          TimesOut times, SchedOut sched, PlanHeader *plan,
@@ -385,30 +387,42 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
 {
     PRS_DYNAMIC_LDS(lds_raw);
     const int b = static_cast<int>(blockIdx.x);
-    if (b < parts.grid[2])
-        bi_group_body<T, kSched, 16>(lds_raw, b, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, parts.rows[2],
-                                     parts.rows_per_group[2]);
-    else if (b < parts.grid[2] + parts.grid[1])
-        bi_group_body<T, kSched, 4>(lds_raw, b - parts.grid[2], cfg, p_max, q_max, model, times, sched, plan, order, 1, retry,
-                                    parts.rows[1], parts.rows_per_group[1]);
-    else
-        bi_group_body<T, kSched, 1>(lds_raw, b - parts.grid[2] - parts.grid[1], cfg, p_max, q_max, model, times, sched, plan,
-                                    order, 0, retry, parts.rows[0], parts.rows_per_group[0]);
+    uint64_t *rows = parts.rows + static_cast<size_t>(b) * parts.rows_per_block;
+    const int first = b < parts.start[2] ? 2 : (b < parts.start[2] + parts.start[1] ? 1 : 0);
+    for (int turn = 0; turn < 3; ++turn) {
+        // turn 0: the class this block starts with; then the remaining classes, largest groups first
+        int cls = first;
+        if (turn > 0) {
+            const int a = first == 2 ? 1 : 2, c = first == 0 ? 1 : 0;
+            cls = turn == 1 ? a : c;
+        }
+        if (!parts.on[cls]) continue;
+        if (cls == 2)
+            bi_group_body<T, kSched, 16>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, rows,
+                                         parts.rows_per_group[2]);
+        else if (cls == 1)
+            bi_group_body<T, kSched, 4>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 1, retry, rows,
+                                        parts.rows_per_group[1]);
+        else
+            bi_group_body<T, kSched, 1>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 0, retry, rows,
+                                        parts.rows_per_group[0]);
+        __syncthreads();
+    }
 }
 
 template <typename T, bool kSched> static void launch_fused(const BiGroupLaunch &L)
 {
     size_t lds = 0;
     for (int k = 0; k < 3; ++k)
-        if (L.parts.grid[k] > 0 && bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16)) > lds) lds = bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16));
-    const int grid = L.parts.grid[0] + L.parts.grid[1] + L.parts.grid[2];
+        if (L.parts.on[k] && bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16)) > lds) lds = bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16));
+    const int grid = L.parts.start[0] + L.parts.start[1] + L.parts.start[2];
     hipLaunchKernelGGL((bi_group_kernel<T, kSched>), dim3(grid), dim3(kWave), lds, L.stream, L.cfg, L.p_max, L.q_max, L.model,
                        L.times, L.sched, L.plan, L.order, L.retry, L.parts);
 }
 
 hipError_t launch_bi_group(const BiGroupLaunch &L)
 {
-    if (L.parts.grid[0] + L.parts.grid[1] + L.parts.grid[2] == 0) return hipSuccess;
+    if (L.parts.start[0] + L.parts.start[1] + L.parts.start[2] == 0) return hipSuccess;
     if (L.cost == PRS_COST_I64) { if (L.want_schedule) launch_fused<int64_t, true>(L); else launch_fused<int64_t, false>(L); }
     else { if (L.want_schedule) launch_fused<double, true>(L); else launch_fused<double, false>(L); }
     return hipGetLastError();
