@@ -265,7 +265,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             // classes the blocks start with
             const ClassSpec &c0 = lay.cls[0];
             int total = c0.grid, enabled = 0;
-            static const int share[3] = {2, 3, 5};                         // tenths of the blocks that start with class 0, 1, 2
+            static const int share[3] = {1, 2, 7};                         // tenths of the blocks that start with class 0, 1, 2
             for (int g = 0; g < 3; ++g) {
                 G.parts.on[g] = lay.cls[g].kind == kBiGroup && lay.cls[g].lpc > 0 && lay.cls[g].rows_per_group > 0 && lay.bi_on[g];
                 G.parts.rows_per_group[g] = lay.cls[g].rows_per_group;
