@@ -61,6 +61,8 @@ def cpu_baseline(host, seconds_hint=20.0):
                       f"completion times with baselines, {dt:.1f} s of wall time"}
 
 
+SEARCH_PROBLEMS = 10000
+
 # per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
 PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 6.1e8, "schedule_uni": 4.97e10, "schedule_bi": 2.48e10,
                           "replay_i32": 4.33e9, "replay_f32": 4.33e9}
@@ -213,6 +215,24 @@ def main():
                                    "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
         "roofline": roof,
     }
+    # outside the timed step: the best-segmentation search (Sections 5.2, 6.1) over the sweep's first 10,000 problems,
+    # ten power-of-two segment counts each
+    sub = prs.DeviceConfigs.from_host(host.take(np.arange(SEARCH_PROBLEMS)))
+    search_ms = {}
+    for m, nm in ((prs.PRS_UNI, "uni"), (prs.PRS_BI, "bi")):
+        wsb = torch.empty(prs.prs_workspace_bytes(prs.PRS_CALL_SEARCH, m, prs.PRS_COST_F64, SEARCH_PROBLEMS, P_MAX, Q_MAX) + 256,
+                          dtype=torch.uint8, device="cuda")
+        prs.optimal_segmentation_batch(sub, m, P_MAX, Q_MAX, workspace=wsb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        prs.optimal_segmentation_batch(sub, m, P_MAX, Q_MAX, workspace=wsb)
+        e1.record()
+        torch.cuda.synchronize()
+        search_ms[nm] = e0.elapsed_time(e1)
+        del wsb
+    out["optimal_segmentation"] = {"problems": SEARCH_PROBLEMS, "candidates_per_problem": int(np.log2(Q_MAX)) + 1,
+                                   "ms": search_ms, "note": "not part of the step or of value"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host)
     print(json.dumps(out))

@@ -53,7 +53,7 @@ typedef enum {
     PRS_CFG_TOO_LARGE = 2,   /* p > p_max, q_req > q_max, or the schedule does not fit pair_capacity */
     PRS_CFG_STALLED = 3      /* time could not advance (a cost vanished against the clock in rounding) */
 } prs_cfg_status;
-typedef enum { PRS_CALL_SIMULATE = 0, PRS_CALL_SCHEDULE = 1, PRS_CALL_REPLAY = 2, PRS_CALL_OFFSETS = 3 } prs_call;
+typedef enum { PRS_CALL_SIMULATE = 0, PRS_CALL_SCHEDULE = 1, PRS_CALL_REPLAY = 2, PRS_CALL_OFFSETS = 3, PRS_CALL_SEARCH = 4 } prs_call;
 
 /* A batch of n configurations, structure of arrays, DEVICE pointers.
  * q_req is the requested number of segments: the segment size is
@@ -156,6 +156,30 @@ int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset,
                      const void *in, int64_t stride_elems, int64_t n_elems, int dtype,
                      void *out, int32_t *status,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Result columns of optimal_segmentation_batch, DEVICE pointers to n entries
+ * each, any of them may be NULL.  T_* have the cost type of the call. */
+typedef struct prs_best {
+    void *T_greedy, *T_pipeline, *T_binary, *T_revopt;      /* smallest completion time over the candidates */
+    int32_t *q_greedy, *q_pipeline, *q_binary, *q_revopt;   /* q_req of the first candidate that reaches it */
+    int32_t *cfg_status;                                    /* prs_cfg_status of the problem */
+} prs_best;
+
+/*
+ * Best segmentation per algorithm (Sections 5.2 and 6.1: every algorithm is
+ * compared at the segment size that suits it best, found by trying sizes).
+ * For each problem (p, m, alpha, beta, gamma) of the batch -- cfg->q_req is
+ * not read and may be NULL -- the candidates q_req = 1, 2, 4, ... (powers of
+ * two up to q_max) are cut as in simulate_completion_batch and timed with the
+ * greedy algorithm of `model`, the pipeline, the binary tree and the reversed
+ * optimal broadcast; out receives per algorithm the smallest completion time
+ * and the candidate that gives it (the smallest such q_req on ties).
+ * Candidates beyond m repeat the unit-size segmentation and never win a tie.
+ * Errors as simulate_completion_batch.
+ */
+int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int cost,
+                               int32_t p_max, int32_t q_max, const prs_best *out,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /* Version of the ABI, bumped on any incompatible change. */
 int prs_abi_version(void);

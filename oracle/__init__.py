@@ -231,3 +231,39 @@ def simulate_batch(cfgs, model, mode=MODE_EVENT | MODE_PRUNE, index=None) -> Bat
         res.q_eff[o] = q
         res.status[o] = s.status
     return res
+
+
+def optimal_segmentation(cfgs, model, q_max, mode=MODE_EVENT | MODE_PRUNE):
+    """Sections 5.2 and 6.1: every algorithm is compared at the segmentation that suits it best.  For each
+    problem (p, m, alpha, beta, gamma) -- cfgs.q_req is not read -- the segment counts 1, 2, 4, ... <= q_max are
+    tried one after the other with the equi-segmentation of Section 2; per algorithm (greedy of `model`,
+    pipeline, binary tree, reversed optimal broadcast) the smallest completion time and the first count that
+    reaches it are returned as dict(T_greedy, q_greedy, ...)."""
+    import copy
+    cands = []
+    q = 1
+    while q <= q_max:
+        cands.append(q)
+        q *= 2
+    n = len(cfgs)
+    names = ("greedy", "pipeline", "binary", "revopt")
+    best_T = {a: None for a in names}
+    best_q = {a: np.zeros(n, np.int32) for a in names}
+    for q in cands:
+        trial = copy.copy(cfgs)
+        trial.q_req = np.full(n, q, np.int32)
+        r = simulate_batch(trial, model, mode)
+        cols = {"greedy": r.T_greedy, "pipeline": r.T_pipeline, "binary": r.T_binary, "revopt": r.T_revopt}
+        for a in names:
+            if best_T[a] is None:
+                best_T[a] = cols[a].copy()
+                best_q[a][:] = q
+            else:
+                better = cols[a] < best_T[a]                      # strictly: ties keep the smaller count
+                best_T[a][better] = cols[a][better]
+                best_q[a][better] = q
+    out = {}
+    for a in names:
+        out["T_" + a] = best_T[a]
+        out["q_" + a] = best_q[a]
+    return out

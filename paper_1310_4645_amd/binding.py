@@ -15,13 +15,13 @@ import numpy as np
 PRS_UNI, PRS_BI = 0, 1
 PRS_COST_I64, PRS_COST_F64 = 0, 1
 PRS_I32, PRS_F32 = 0, 1
-PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS = 0, 1, 2, 3
+PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS, PRS_CALL_SEARCH = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("prs_abi_version", "prs_workspace_bytes", "simulate_completion_batch", "prs_pair_offsets",
-           "greedy_schedule_batch", "replay_reduction")
+           "greedy_schedule_batch", "replay_reduction", "optimal_segmentation_batch")
 
 
 class PrsError(RuntimeError):
@@ -36,6 +36,11 @@ class _Configs(C.Structure):
 class _Times(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("greedy", "binomial", "pipeline", "binary", "revopt", "butterfly",
                                           "lower_bound", "q_eff", "cfg_status")]
+
+
+class _Best(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("T_greedy", "T_pipeline", "T_binary", "T_revopt", "q_greedy", "q_pipeline",
+                                          "q_binary", "q_revopt", "cfg_status")]
 
 
 def library_path() -> str:
@@ -68,6 +73,9 @@ def load_library():
         lib.replay_reduction.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                          C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.optimal_segmentation_batch.restype = C.c_int
+        lib.optimal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
+                                                   C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p]
         _LIB = lib
     return _LIB
 
@@ -153,6 +161,29 @@ def simulate_completion_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max:
     rc = lib.simulate_completion_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, C.byref(times),
                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
     _check(rc, "simulate_completion_batch")
+    out["_workspace"] = ws
+    return out
+
+
+def optimal_segmentation_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int, workspace=None):
+    """Best power-of-two segment count per algorithm.  Returns a dict of device tensors: T_greedy, T_pipeline,
+    T_binary, T_revopt (cost type), q_greedy, q_pipeline, q_binary, q_revopt, cfg_status (int32).  cfg.q_req is
+    not read."""
+    import torch
+    lib = load_library()
+    n = len(cfg)
+    dev = cfg.p.device
+    tt = torch.int64 if cfg.cost == PRS_COST_I64 else torch.float64
+    out = {k: torch.empty(n, dtype=tt, device=dev) for k in ("T_greedy", "T_pipeline", "T_binary", "T_revopt")}
+    out.update({k: torch.empty(n, dtype=torch.int32, device=dev)
+                for k in ("q_greedy", "q_pipeline", "q_binary", "q_revopt", "cfg_status")})
+    need = prs_workspace_bytes(PRS_CALL_SEARCH, model, cfg.cost, n, p_max, q_max)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    best = _Best(*[out[k].data_ptr() for k, _ in _Best._fields_])
+    cs = cfg.struct()
+    rc = lib.optimal_segmentation_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, C.byref(best),
+                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+    _check(rc, "optimal_segmentation_batch")
     out["_workspace"] = ws
     return out
 

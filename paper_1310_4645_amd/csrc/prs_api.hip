@@ -291,6 +291,83 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
     return PRS_OK;
 }
 
+// ---- best segmentation per algorithm: candidates q_req = 2^c, c < n_cand, for every problem ----------
+template <typename T>
+__global__ void search_expand(ConfigArrays in, int64_t n, int n_cand, int32_t *p, int32_t *q_req, int64_t *m, T *alpha, T *beta,
+                              T *gamma)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (idx >= n * n_cand) return;
+    const int64_t i = idx / n_cand;
+    const int c = static_cast<int>(idx - i * n_cand);
+    p[idx] = in.p[i];
+    q_req[idx] = 1 << c;
+    m[idx] = in.m[i];
+    alpha[idx] = static_cast<const T *>(in.alpha)[i];
+    beta[idx] = static_cast<const T *>(in.beta)[i];
+    gamma[idx] = static_cast<const T *>(in.gamma)[i];
+}
+
+struct BestOut {
+    void *T[4];
+    int32_t *q[4];
+    int32_t *cfg_status;
+};
+
+template <typename T>
+__global__ void search_pick(int64_t n, int n_cand, const T *greedy, const T *pipeline, const T *binary, const T *revopt,
+                            const int32_t *status, BestOut out)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const T *col[4] = {greedy, pipeline, binary, revopt};
+    const int32_t st = status[i * n_cand];                         // the problem itself: candidate q_req = 1
+    if (out.cfg_status) out.cfg_status[i] = st;
+    for (int a = 0; a < 4; ++a) {
+        T best = CostTraits<T>::bad();
+        int32_t best_q = -1;
+        if (st == PRS_CFG_OK) {
+            for (int c = 0; c < n_cand; ++c) {
+                if (status[i * n_cand + c] != PRS_CFG_OK) continue;
+                const T v = col[a][i * n_cand + c];
+                if (best_q < 0 || v < best) { best = v; best_q = 1 << c; }
+            }
+        }
+        if (out.T[a]) static_cast<T *>(out.T[a])[i] = best;
+        if (out.q[a]) out.q[a][i] = best_q;
+    }
+}
+
+static int search_candidates(int32_t q_max)
+{
+    int c = 1;
+    while ((INT64_C(1) << c) <= q_max) ++c;
+    return c;                                                      // 1, 2, ..., 2^(c-1) <= q_max
+}
+
+struct SearchLayout {
+    int n_cand;
+    int64_t n_exp;
+    size_t p, q_req, m, alpha, beta, gamma, greedy, pipeline, binary, revopt, status, sim, total;
+};
+
+static SearchLayout make_search_layout(int model, int64_t n, int32_t p_max, int32_t q_max)
+{
+    SearchLayout S;
+    S.n_cand = search_candidates(q_max);
+    S.n_exp = (n < 1 ? 1 : n) * S.n_cand;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    const size_t e = static_cast<size_t>(S.n_exp);
+    S.p = take(e * 4); S.q_req = take(e * 4); S.m = take(e * 8);
+    S.alpha = take(e * 8); S.beta = take(e * 8); S.gamma = take(e * 8);
+    S.greedy = take(e * 8); S.pipeline = take(e * 8); S.binary = take(e * 8); S.revopt = take(e * 8);
+    S.status = take(e * 4);
+    S.sim = off;
+    S.total = off + make_layout(PRS_CALL_SIMULATE, model, S.n_exp, p_max, q_max).total;
+    return S;
+}
+
 }  // namespace prs
 
 using namespace prs;
@@ -305,6 +382,7 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
     if (n < 0 || p_max < 2 || q_max < 1) return 0;
     if (call == PRS_CALL_REPLAY) return replay_workspace_bytes(p_max, q_max);
     if (call == PRS_CALL_OFFSETS) return kHeaderBytes;
+    if (call == PRS_CALL_SEARCH) return make_search_layout(model, n, p_max, q_max).total;
     if (call != PRS_CALL_SIMULATE && call != PRS_CALL_SCHEDULE) return 0;
     return make_layout(call, model, n, p_max, q_max).total;
 }
@@ -317,6 +395,56 @@ int simulate_completion_batch(const prs_configs *cfg, int64_t n, int model, int 
                out->butterfly, out->lower_bound, out->q_eff, out->cfg_status};
     SchedOut s{};
     return run_greedy(PRS_CALL_SIMULATE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream);
+}
+
+int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
+                               const prs_best *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cfg || !out || n < 0 || n >= (INT64_C(1) << 26) || (model != PRS_UNI && model != PRS_BI) ||
+        (cost != PRS_COST_I64 && cost != PRS_COST_F64) || p_max < 2 || p_max > (1 << 20) || q_max < 1 || q_max > (1 << 20))
+        return PRS_EINVAL;
+    if (n > 0 && (!cfg->p || !cfg->m || !cfg->alpha || !cfg->beta || !cfg->gamma)) return PRS_EINVAL;
+    if (n == 0) return PRS_OK;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
+    const SearchLayout S = make_search_layout(model, n, p_max, q_max);
+    if (workspace_bytes < S.total) return PRS_ENOSPC;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const ConfigArrays in{cfg->p, nullptr, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
+    int32_t *ep = reinterpret_cast<int32_t *>(ws + S.p), *eq = reinterpret_cast<int32_t *>(ws + S.q_req);
+    int64_t *em = reinterpret_cast<int64_t *>(ws + S.m);
+    const int64_t n_exp = n * S.n_cand;
+    const unsigned blocks = static_cast<unsigned>((n_exp + 255) / 256);
+    if (cost == PRS_COST_I64)
+        hipLaunchKernelGGL((search_expand<int64_t>), dim3(blocks), dim3(256), 0, st, in, n, S.n_cand, ep, eq, em,
+                           reinterpret_cast<int64_t *>(ws + S.alpha), reinterpret_cast<int64_t *>(ws + S.beta),
+                           reinterpret_cast<int64_t *>(ws + S.gamma));
+    else
+        hipLaunchKernelGGL((search_expand<double>), dim3(blocks), dim3(256), 0, st, in, n, S.n_cand, ep, eq, em,
+                           reinterpret_cast<double *>(ws + S.alpha), reinterpret_cast<double *>(ws + S.beta),
+                           reinterpret_cast<double *>(ws + S.gamma));
+    if (hipGetLastError() != hipSuccess) return PRS_EDEVICE;
+    const prs_configs exp_cfg{ep, eq, em, ws + S.alpha, ws + S.beta, ws + S.gamma};
+    TimesOut t{ws + S.greedy, nullptr, ws + S.pipeline, ws + S.binary, ws + S.revopt, nullptr, nullptr, nullptr,
+               reinterpret_cast<int32_t *>(ws + S.status)};
+    SchedOut s{};
+    const int rc = run_greedy(PRS_CALL_SIMULATE, &exp_cfg, n_exp, model, cost, p_max, q_max, t, s, ws + S.sim,
+                              workspace_bytes - S.sim, stream);
+    if (rc != PRS_OK) return rc;
+    BestOut b{{out->T_greedy, out->T_pipeline, out->T_binary, out->T_revopt},
+              {out->q_greedy, out->q_pipeline, out->q_binary, out->q_revopt}, out->cfg_status};
+    const unsigned pblocks = static_cast<unsigned>((n + 255) / 256);
+    if (cost == PRS_COST_I64)
+        hipLaunchKernelGGL((search_pick<int64_t>), dim3(pblocks), dim3(256), 0, st, n, S.n_cand,
+                           reinterpret_cast<const int64_t *>(ws + S.greedy), reinterpret_cast<const int64_t *>(ws + S.pipeline),
+                           reinterpret_cast<const int64_t *>(ws + S.binary), reinterpret_cast<const int64_t *>(ws + S.revopt),
+                           reinterpret_cast<const int32_t *>(ws + S.status), b);
+    else
+        hipLaunchKernelGGL((search_pick<double>), dim3(pblocks), dim3(256), 0, st, n, S.n_cand,
+                           reinterpret_cast<const double *>(ws + S.greedy), reinterpret_cast<const double *>(ws + S.pipeline),
+                           reinterpret_cast<const double *>(ws + S.binary), reinterpret_cast<const double *>(ws + S.revopt),
+                           reinterpret_cast<const int32_t *>(ws + S.status), b);
+    return hipGetLastError() == hipSuccess ? PRS_OK : PRS_EDEVICE;
 }
 
 int prs_pair_offsets(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t q_max, int64_t *pair_offset,

@@ -297,6 +297,33 @@ def test_large_p_sample(prs, model):
     assert np.all(_np(got["cfg_status"]) == 0)
 
 
+# --------------------------------------------------------------------------- best segmentation per algorithm
+@pytest.mark.parametrize("model", [0, 1])
+@pytest.mark.parametrize("cost", ["i64", "f64"])
+def test_optimal_segmentation_matches_trying_each_count(prs, model, cost):
+    rng = np.random.default_rng(500 + model)
+    n = 150
+    p = rng.integers(2, 90, n).astype(np.int32)
+    m = rng.integers(1, 3000, n).astype(np.int64)
+    if cost == "i64":
+        al, be, ga = (rng.integers(0, 60, n).astype(np.int64), rng.integers(1, 4, n).astype(np.int64),
+                      rng.integers(0, 4, n).astype(np.int64))
+    else:
+        al, be, ga = 10.0 ** rng.uniform(-6, -4, n), 10.0 ** rng.uniform(-10, -8, n), 10.0 ** rng.uniform(-11, -9, n)
+    p[:3] = [2, 3, 1]                                                   # the last one is not a valid problem
+    host = prs_inputs.SweepConfigs(p, np.zeros(n, np.int32), m, al, be, ga, cost)
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.optimal_segmentation_batch(dev, model, 128, 32)
+    _sync()
+    ok = np.ones(n, bool); ok[2] = False
+    ref = O.optimal_segmentation(host.take(np.nonzero(ok)[0]), model, 32)
+    for key in ("greedy", "pipeline", "binary", "revopt"):
+        assert np.array_equal(_np(got["T_" + key])[ok], ref["T_" + key]), key
+        assert np.array_equal(_np(got["q_" + key])[ok], ref["q_" + key]), key
+    st = _np(got["cfg_status"])
+    assert st[2] == 1 and np.all(st[ok] == 0) and _np(got["q_greedy"])[2] == -1
+
+
 # --------------------------------------------------------------------------- replay
 def _replay_case(prs, p, sizes, model, seg_off, dtype, cost=("i64", 2, 1, 1), strided=False):
     import torch

@@ -406,3 +406,51 @@ def test_replay_follows_the_schedule_order():
     star = O.replay(3, off, [1, 2], [0, 0], [0, 0], buf)
     assert chain[0] == np.float32(1.0) + np.float32(2.0 ** -23)
     assert star[0] == np.float32(1.0)
+
+
+# --------------------------------------------------------------------------- best segmentation (Sections 5.2, 6.1)
+def _table1_pipeline_uni(p, q, m, a, b, g):
+    sz = -(-m // q)
+    qe = -(-m // sz)
+    return (p - 1 + 2 * (qe - 1)) * (a + b * sz + g * sz)            # Table I, unidirectional pipeline
+
+
+def test_best_segmentation_is_the_minimum_over_the_candidates():
+    """The search is pinned by brute force: Table I's pipeline time written out here and minimised over the same
+    candidates gives the same time and count; the greedy optimum is what trying each count one by one gives;
+    with a single candidate the search is the plain simulation; a larger candidate set never does worse."""
+    rng = np.random.default_rng(11)
+    n = 40
+    p = rng.integers(2, 48, n).astype(np.int32)
+    m = rng.integers(1, 400, n).astype(np.int64)
+    al = rng.integers(0, 40, n).astype(np.int64); be = rng.integers(1, 4, n).astype(np.int64); ga = rng.integers(0, 4, n).astype(np.int64)
+    host = prs_inputs.SweepConfigs(p, np.full(n, 7, np.int32), m, al, be, ga, "i64")      # q_req must not matter
+    got = O.optimal_segmentation(host, O.UNI, 64)
+    cands = [1, 2, 4, 8, 16, 32, 64]
+    for i in range(n):
+        vals = [_table1_pipeline_uni(int(p[i]), q, int(m[i]), int(al[i]), int(be[i]), int(ga[i])) for q in cands]
+        assert got["T_pipeline"][i] == min(vals)
+        assert got["q_pipeline"][i] == cands[vals.index(min(vals))]
+        gv = [O.uni_greedy(int(p[i]), O.equi_sizes(int(m[i]), q), int(al[i]), int(be[i]), int(ga[i]), "i64", want_schedule=False).T
+              for q in cands]
+        assert got["T_greedy"][i] == min(gv) and got["q_greedy"][i] == cands[gv.index(min(gv))]
+    one = O.optimal_segmentation(host, O.UNI, 1)
+    host1 = prs_inputs.SweepConfigs(p, np.ones(n, np.int32), m, al, be, ga, "i64")
+    assert np.array_equal(one["T_greedy"], O.simulate_batch(host1, O.UNI).T_greedy) and np.all(one["q_greedy"] == 1)
+    more = O.optimal_segmentation(host, O.UNI, 256)
+    for a in ("greedy", "pipeline", "binary", "revopt"):
+        assert np.all(more["T_" + a] <= got["T_" + a])
+    # Theorem 1 at every segmentation: the greedy optimum is not above any in-order algorithm's optimum
+    assert np.all(got["T_greedy"] <= got["T_pipeline"]) and np.all(got["T_greedy"] <= got["T_binary"])
+
+
+def test_best_segmentation_bidirectional_meets_table3_at_its_best_count():
+    """Bi-greedy at equal segments meets the reversed optimal broadcast (Table III), so their optima over the
+    candidates that divide m coincide."""
+    n = 24
+    p = np.arange(2, 2 + n).astype(np.int32)
+    m = np.full(n, 64, np.int64)                                       # every power-of-two count divides m
+    host = prs_inputs.SweepConfigs(p, np.ones(n, np.int32), m, np.full(n, 9, np.int64), np.full(n, 2, np.int64),
+                                   np.full(n, 1, np.int64), "i64")
+    got = O.optimal_segmentation(host, O.BI, 64)
+    assert np.array_equal(got["T_greedy"], got["T_revopt"]) and np.array_equal(got["q_greedy"], got["q_revopt"])
