@@ -74,6 +74,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     T holdX = 0; int32_t holdI = 0; // entry of the running value held back (largest index so far)
     T lastS = 0;                    // running value of my stream (0 before the first pair of a segment)
     T lastBx = 0; int brun = 0;     // value of the last B entry pushed, first pair of that value (relative)
+    int32_t lastWi = 0, lastBi = 0; // sender of the last stream entry written, receiver of the last B entry
     T prevRoot = 0, cc = 0, gg = 0;
     bool farA = false, farB = false, anyFar = false;
     T la0 = 0, la1 = 0, lb0 = 0, lb1 = 0;
@@ -227,8 +228,9 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 // over the LDS slot of the one kRingS places back, so that one is read from the workspace.
                 const int rows_done = w & ~3;
                 int at = w;
+                const bool in_order = !(lastWi > wi);                         // the usual case: nothing to move, nothing to read
                 for (;;) {
-                    if (at <= runStart) break;
+                    if (at <= runStart || in_order) break;
                     const int32_t mv = w + 2 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
                     if (!(mv > wi)) break;
                     if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
@@ -238,6 +240,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 ringX[(wtot & M) * kWave + lane] = wx;
                 if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = wi;
                 if (at < rows_done) myI[at] = wi;
+                if (at == w) lastWi = wi;                                     // index of the last entry written
                 ++w; ++wtot;
                 if ((w & 3) == 0) {
                     T rx4[4]; int32_t ri4[4];
@@ -260,8 +263,9 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 int at = ns;
                 const int ib = bpos - segBase;
                 const int lo = brun > ib ? brun : ib;
+                const bool in_order = !(lastBi > rcv);
                 for (;;) {
-                    if (at <= lo) break;
+                    if (at <= lo || in_order) break;
                     const int32_t mv = ns + 2 - at <= kRingS ? ringB[((segBase + at - 1) & M) * kWave + lane] : bufB[at - 1];
                     if (!(mv > rcv)) break;
                     if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = mv;
@@ -270,6 +274,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 }
                 if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = rcv;
                 if (at < rows_done) bufB[at] = rcv;
+                if (at == ns) lastBi = rcv;                                   // receiver of the last B entry
                 if (((ns + 1) & 3) == 0) {
                     int32_t rb4[4];
 #pragma unroll
