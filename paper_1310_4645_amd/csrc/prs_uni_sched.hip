@@ -9,8 +9,9 @@
 //    can round to the same double.  The producer therefore holds back the entry with the largest index of
 //    the running value, writes the others in index order (inserting a late smaller index where it
 //    belongs), and the next segment only reads entries below the running value: they are final.
-//  - the root's final state (largest value, index 0) is a third source next to A and B: it sorts before
-//    stream entries of equal value, so it is not part of the stream (p - 1 entries per segment).
+//  - the root's final state (largest value, index 0) closes the stream of a segment as in the value pipeline,
+//    but it sorts before stream entries of equal value (they occur when tcomp vanishes against the clock),
+//    so it goes through the same insertion.
 //  - B needs the receiver's index per pair, kept in a per-lane array; its values are still S + tcomp.
 //    Equal B values are kept in index order by the same insertion.
 #include "prs_device.h"
@@ -62,20 +63,20 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     int64_t ci = 0, out_base = 0;
     int p = 2, q = 1;
     T c_full = 0, g_full = 0, c_last = 0, g_last = 0;
-    // ---- per-lane state.  Positions count stream entries (= pairs) from the start of the configuration:
-    // every finished segment adds p - 1 of them.
+    // ---- per-lane state.  Positions count stream entries from the start of the configuration: every finished
+    // segment adds p of them (one per pair and the root's); pair i of a segment shares position i with entry i.
     int k = 0, par = 0, apar = 0;
     int wtot = 0, segBase = 0;      // entries written; the same at the start of my segment
     int ns = 0;                     // pairs done in my segment (entries written + the one held back)
     int runStart = 0;               // first entry of the running value, relative to segBase: entries before it are final
     int apos = 0, astart = 0;       // next entry of my input stream; its first entry
     int bpos = 0;                   // next pair of my segment whose B entry is unread (absolute)
-    bool rootUsed = false, hold = false;
+    bool hold = false;
     T holdX = 0; int32_t holdI = 0; // entry of the running value held back (largest index so far)
     T lastS = 0;                    // running value of my stream (0 before the first pair of a segment)
     T lastBx = 0; int brun = 0;     // value of the last B entry pushed, first pair of that value (relative)
     int32_t lastWi = 0, lastBi = 0; // sender of the last stream entry written, receiver of the last B entry
-    T prevRoot = 0, cc = 0, gg = 0;
+    T cc = 0, gg = 0;
     bool farA = false, farB = false, anyFar = false;
     T la0 = 0, la1 = 0, lb0 = 0, lb1 = 0;
     int32_t lai0 = 0, lai1 = 0, lbi0 = 0, lbi1 = 0;
@@ -111,7 +112,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                     c_full = c.c_full; g_full = c.g_full; c_last = c.c_last; g_last = c.g_last;
                     k = gl; par = 0; apar = gl == 0 ? 1 : 0;
                     wtot = segBase = ns = runStart = apos = astart = bpos = brun = 0;
-                    rootUsed = hold = false; lastS = 0; prevRoot = 0;
+                    hold = false; lastS = 0;
                     farA = farB = false;
                     cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
                 }
@@ -124,15 +125,14 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
 
         // ---------------------------------------------------------------- what my producer has done so far
         int pw = wtot, pfinal = segBase + runStart;
-        T plast = lastS, proot = prevRoot;
+        T plast = lastS;
         if (G > 1) {
             pw = __shfl(wtot, prod, kWave);
             pfinal = __shfl(segBase + runStart, prod, kWave);
             plast = __shfl(lastS, prod, kWave);
-            proot = __shfl(prevRoot, prod, kWave);
         }
         const bool first = k == 0;
-        const int aend = astart + n1;
+        const int aend = astart + p;
         const int availEnd = first ? aend : (pfinal < aend ? pfinal : aend);   // entries below the producer's running value are final
         const bool complete = first || pfinal >= aend;
         // entries not final yet are >= the running value of a producer that is on my stream
@@ -149,39 +149,25 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             if (farA) { a0 = la0; a1 = la1; a0i = lai0; a1i = lai1; }
             if (farB) { sb0 = lb0; sb1 = lb1; b0i = lbi0; b1i = lbi1; }
         }
-        if (first) { a0 = 0; a1 = 0; a0i = apos + 1; a1i = apos + 2; }      // first segment: processors 1..p-1 at time 0
+        if (first) { a0 = 0; a1 = 0; a0i = apos; a1i = apos + 1; }          // first segment: processors 0..p-1 at time 0
         const bool ha0 = apos < availEnd, ha1 = apos + 1 < availEnd;
         // B value i is stream value i; the newest one may still be the held entry of the running value
         if (!(bpos < wtot)) sb0 = lastS;
         if (!(bpos + 1 < wtot)) sb1 = lastS;
         const T b0 = wrap_add<T>(sb0, gg), b1 = wrap_add<T>(sb1, gg);
         const bool hb0 = bpos < segBase + ns, hb1 = bpos + 1 < segBase + ns;
-        // the root of this segment: at time 0 in the first segment, else the previous segment's root
-        const bool hr = !rootUsed && complete;
-        const T rx = first ? T(0) : proot;
 
-        // ---------------------------------------------------------------- two smallest keys among A, B and the root
-        int s1 = -1, s2 = -1;                  // 0: A, 1: B, 2: root
-        T e1x = 0, e2x = 0; int32_t e1i = 0, e2i = 0;
-        {
-            T bx = 0; int32_t bi = 0;
-            if (ha0) { s1 = 0; bx = a0; bi = a0i; }
-            if (hb0 && (s1 < 0 || key_less<T>(b0, b0i, bx, bi))) { s1 = 1; bx = b0; bi = b0i; }
-            if (hr && (s1 < 0 || key_less<T>(rx, 0, bx, bi))) { s1 = 2; bx = rx; bi = 0; }
-            e1x = bx; e1i = bi;
-            // second: heads after removing the first
-            const bool ca = s1 == 0 ? ha1 : ha0, cb = s1 == 1 ? hb1 : hb0, cr = hr && s1 != 2;
-            const T ax = s1 == 0 ? a1 : a0; const int32_t ai = s1 == 0 ? a1i : a0i;
-            const T bbx = s1 == 1 ? b1 : b0; const int32_t bbi = s1 == 1 ? b1i : b0i;
-            T cx = 0; int32_t cid = 0;
-            if (ca) { s2 = 0; cx = ax; cid = ai; }
-            if (cb && (s2 < 0 || key_less<T>(bbx, bbi, cx, cid))) { s2 = 1; cx = bbx; cid = bbi; }
-            if (cr && (s2 < 0 || key_less<T>(rx, 0, cx, cid))) { s2 = 2; cx = rx; cid = 0; }
-            e2x = cx; e2i = cid;
-        }
+        // ---------------------------------------------------------------- the two smallest keys of A and B
+        const bool x = ha0 && !(hb0 && key_less<T>(b0, b0i, a0, a0i));        // the smallest is A's head
+        const bool hu = x ? ha1 : ha0, hv = x ? hb0 : hb1;                     // heads after removing it
+        const T ux = x ? a1 : a0, vx = x ? b0 : b1;
+        const int32_t ui = x ? a1i : a0i, vi = x ? b0i : b1i;
+        const bool y = hu && !(hv && key_less<T>(vx, vi, ux, ui));            // the second smallest comes from A
+        const int32_t e1i = x ? a0i : b0i;
+        const T e2x = y ? ux : vx;
+        const int32_t e2i = y ? ui : vi;
         // an entry that is not final yet could come first
-        const bool ok = active && s1 >= 0 && s2 >= 0 && (complete || e2x < front);
-        (void)e1x;
+        const bool ok = active && (ha0 || hb0) && (hu || hv) && (complete || e2x < front);
 
         if (ok) {
             const T t = e2x, tc = wrap_add<T>(t, cc), tr = wrap_add<T>(tc, gg);
@@ -211,26 +197,18 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             T *const myX = bufX(lane, par);
             int32_t *const myI = bufI(lane, par);
             int w = wtot - segBase;                                           // entries written in this segment
-            // ---- stream entry (tc, snd): keep the largest index of the running value back
-            T wx = 0; int32_t wi = 0; bool wr = false;
-            if (hold && tc == holdX) {
-                if (snd > holdI) { wx = holdX; wi = holdI; holdI = snd; } else { wx = tc; wi = snd; }
-                wr = true;
-            } else {
-                if (hold) { wx = holdX; wi = holdI; wr = true; }
-                hold = true; holdX = tc; holdI = snd;
-            }
-            // Entries reach the workspace in rows of four (16-byte stores) once a row is complete; younger
-            // ones are in LDS only.  What is read from the workspace is always more than a row old.
-            if (wr) {
-                // entries of the running value are written in rising index order; a smaller index that comes
-                // late is inserted (the next segment does not read the running value yet).  The new entry takes
-                // over the LDS slot of the one kRingS places back, so that one is read from the workspace.
+            // Writes one stream entry.  Entries of the running value are written in rising index order; a
+            // smaller index that comes late is inserted (the next segment does not read the running value
+            // yet).  Entries reach the workspace in rows of four (16-byte stores) once a row is complete;
+            // younger ones are in LDS only, and what is read from the workspace is always more than a row old.
+            // The new entry takes over the LDS slot of the one kRingS places back, so an insertion that
+            // reaches that far reads the workspace copy.
+            auto put = [&](T wx, int32_t wi, int run_from) {
                 const int rows_done = w & ~3;
                 int at = w;
                 const bool in_order = !(lastWi > wi);                         // the usual case: nothing to move, nothing to read
                 for (;;) {
-                    if (at <= runStart || in_order) break;
+                    if (at <= run_from || in_order) break;
                     const int32_t mv = w + 2 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
                     if (!(mv > wi)) break;
                     if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
@@ -252,7 +230,17 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                     __builtin_memcpy(myX + w - 4, rx4, 32);
                     __builtin_memcpy(myI + w - 4, ri4, 16);
                 }
+            };
+            // ---- stream entry (tc, snd): keep the largest index of the running value back
+            T wx = 0; int32_t wi = 0; bool wr = false;
+            if (hold && tc == holdX) {
+                if (snd > holdI) { wx = holdX; wi = holdI; holdI = snd; } else { wx = tc; wi = snd; }
+                wr = true;
+            } else {
+                if (hold) { wx = holdX; wi = holdI; wr = true; }
+                hold = true; holdX = tc; holdI = snd;
             }
+            if (wr) put(wx, wi, runStart);
             if (!(tc == lastS) || ns == 0) runStart = w;                      // entries before the running value are final
             lastS = tc;
             // ---- B entry (tr, rcv) of pair ns; equal values keep rising index order
@@ -283,26 +271,25 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 }
             }
             // ---- consume
-            if (s1 == 2 || s2 == 2) rootUsed = true;
-            const int dA = (s1 == 0 ? 1 : 0) + (s2 == 0 ? 1 : 0), dB = (s1 == 1 ? 1 : 0) + (s2 == 1 ? 1 : 0);
-            apos += dA; bpos += dB;
+            const int dA = (x ? 1 : 0) + (y ? 1 : 0);
+            apos += dA; bpos += 2 - dA;
             ++ns;
             if (ns == n1) {                                                   // segment done: flush, hand over
-                // the held index is the largest of its value: it is the last entry (w = n1 - 1)
-                ringX[(wtot & M) * kWave + lane] = holdX; ringI[(wtot & M) * kWave + lane] = holdI;
-                ++wtot;
-                for (int j = w & ~3; j <= w; ++j) {                           // the last row, complete or not
+                put(holdX, holdI, runStart);                                  // the held index is the largest of its value
+                hold = false;
+                // the root's final state: the largest value, in front of entries of the same value
+                if (!(tr == lastS)) runStart = w;
+                put(tr, 0, runStart);
+                for (int j = w & ~3; j < w; ++j) {                            // the last row of the stream if it is not complete
                     const int rr = ((segBase + j) & M) * kWave + lane;
                     myX[j] = ringX[rr]; myI[j] = ringI[rr];
-                    bufB[j] = ringB[rr];
                 }
-                hold = false;
-                prevRoot = tr;
+                for (int j = (n1 - 1) & ~3; j < n1; ++j) bufB[j] = ringB[((segBase + j) & M) * kWave + lane];
                 if (k == q - 1 && sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = tr;
                 k += G; par ^= 1;
                 segBase = wtot; ns = 0; runStart = 0; brun = 0; bpos = wtot;
-                rootUsed = false; lastS = 0;
-                astart = gl == 0 ? segBase - n1 : segBase;                    // the stream my producer writes in its current round
+                lastS = 0;
+                astart = gl == 0 ? segBase - p : segBase;                     // the stream my producer writes in its current round
                 apar = gl == 0 ? par ^ 1 : par;
                 apos = astart;
                 cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
@@ -319,7 +306,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
         if (anyFar) {
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
             if (farA) {
-                const int i0 = apos - astart < n1 ? apos - astart : n1 - 1, i1 = i0 + 1 < n1 ? i0 + 1 : n1 - 1;
+                const int i0 = apos - astart < p ? apos - astart : p - 1, i1 = i0 + 1 < p ? i0 + 1 : p - 1;
                 la0 = bufX(prod, apar)[i0]; lai0 = bufI(prod, apar)[i0];
                 la1 = bufX(prod, apar)[i1]; lai1 = bufI(prod, apar)[i1];
             }
