@@ -22,7 +22,9 @@ namespace prs {
 constexpr int kRingS = 32;           // stream entries per lane kept in LDS
 constexpr int kNearS = kRingS - 5;   // entries this close behind the writer are read from LDS in the next iteration
 
-size_t uni_sched_lds_bytes() { return static_cast<size_t>(kRingS) * kWave * 16 + static_cast<size_t>(kWave) * 4 * 16; }
+constexpr int kStage = 8;            // pairs per lane waiting in LDS for their 16-byte stores
+
+size_t uni_sched_lds_bytes() { return static_cast<size_t>(kRingS) * kWave * 16 + static_cast<size_t>(kWave) * kStage * 16; }
 // per lane: stream values [2][p], stream indices [2][p], receiver indices [p]
 size_t uni_sched_slot_bytes(int32_t p_cap)
 {
@@ -43,9 +45,9 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     T *ringX = reinterpret_cast<T *>(lds_raw);                                   // [kRingS][64] stream values
     int32_t *ringI = reinterpret_cast<int32_t *>(ringX + kRingS * kWave);        // [kRingS][64] stream sender indices
     int32_t *ringB = ringI + kRingS * kWave;                                     // [kRingS][64] receiver index per pair
-    T *stT = reinterpret_cast<T *>(ringB + kRingS * kWave);                      // [64][4] start times of the lane's last pairs
-    int32_t *stS = reinterpret_cast<int32_t *>(stT + kWave * 4);                 // [64][4] their senders
-    int32_t *stD = stS + kWave * 4;                                              // [64][4] their receivers
+    T *stT = reinterpret_cast<T *>(ringB + kRingS * kWave);                      // [64][kStage] start times of the lane's last pairs
+    int32_t *stS = reinterpret_cast<int32_t *>(stT + kWave * kStage);            // [64][kStage] their senders
+    int32_t *stD = stS + kWave * kStage;                                         // [64][kStage] their receivers
     const int lane = lane_id(), gl = lane & (G - 1), gbase = lane & ~(G - 1);
     const int prod = gbase | ((gl + G - 1) & (G - 1));
     const uint64_t gmask = (G == 64 ? ~UINT64_C(0) : ((UINT64_C(1) << G) - 1)) << gbase;
@@ -76,6 +78,11 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     T lastS = 0;                    // running value of my stream (0 before the first pair of a segment)
     T lastBx = 0; int brun = 0;     // value of the last B entry pushed, first pair of that value (relative)
     int32_t lastWi = 0, lastBi = 0; // sender of the last stream entry written, receiver of the last B entry
+    // Stream entries, receiver indices and pairs leave LDS in rows of four (16-byte stores).  Rows are written
+    // every fourth iteration of the wavefront, by all lanes at once: done per lane whenever its row fills, the
+    // row code would run in almost every iteration for a few lanes each.
+    int fW = 0, fB = 0, fO = 0;     // entries / receivers / pairs of my segment that have reached the workspace (multiples of 4)
+    int iter = 0;
     T cc = 0, gg = 0;
     bool farA = false, farB = false, anyFar = false;
     T la0 = 0, la1 = 0, lb0 = 0, lb1 = 0;
@@ -112,6 +119,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                     c_full = c.c_full; g_full = c.g_full; c_last = c.c_last; g_last = c.g_last;
                     k = gl; par = 0; apar = gl == 0 ? 1 : 0;
                     wtot = segBase = ns = runStart = apos = astart = bpos = brun = 0;
+                    fW = fB = fO = 0;
                     hold = false; lastS = 0;
                     farA = farB = false;
                     cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
@@ -173,38 +181,22 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             const T t = e2x, tc = wrap_add<T>(t, cc), tr = wrap_add<T>(tc, gg);
             int32_t snd = e1i, rcv = e2i;
             if (e1i == 0) { snd = e2i; rcv = 0; }                             // the root never sends (Lemma 1 (ii))
-            // ---- the pair goes to a four-pair staging row of the lane; full rows leave as 16-byte stores
+            // ---- the pair waits in the lane's staging rows
             {
-                const int slot4 = ns & 3, row = lane * 4;
-                stS[row + slot4] = snd; stD[row + slot4] = rcv; stT[row + slot4] = t;
-                const int64_t o = out_base + static_cast<int64_t>(k) * n1 + ns;
-                if (slot4 == 3) {
-                    const int64_t o4 = o - 3;
-                    if (sched.src) __builtin_memcpy(sched.src + o4, stS + row, 16);
-                    if (sched.dst) __builtin_memcpy(sched.dst + o4, stD + row, 16);
-                    if (sched.seg) { const int32_t kk[4] = {k, k, k, k}; __builtin_memcpy(sched.seg + o4, kk, 16); }
-                    if (sched.tstart) __builtin_memcpy(static_cast<T *>(sched.tstart) + o4, stT + row, 32);
-                } else if (ns == n1 - 1) {                                    // the segment ends inside a row
-                    for (int j = 0; j <= slot4; ++j) {
-                        const int64_t oj = o - slot4 + j;
-                        if (sched.src) sched.src[oj] = stS[row + j];
-                        if (sched.dst) sched.dst[oj] = stD[row + j];
-                        if (sched.seg) sched.seg[oj] = k;
-                        if (sched.tstart) static_cast<T *>(sched.tstart)[oj] = stT[row + j];
-                    }
-                }
+                const int slot = lane * kStage + (ns & (kStage - 1));
+                stS[slot] = snd; stD[slot] = rcv; stT[slot] = t;
             }
             T *const myX = bufX(lane, par);
             int32_t *const myI = bufI(lane, par);
             int w = wtot - segBase;                                           // entries written in this segment
             // Writes one stream entry.  Entries of the running value are written in rising index order; a
             // smaller index that comes late is inserted (the next segment does not read the running value
-            // yet).  Entries reach the workspace in rows of four (16-byte stores) once a row is complete;
-            // younger ones are in LDS only, and what is read from the workspace is always more than a row old.
+            // yet).  Entries that have reached the workspace (the first fW) are corrected there as well; what
+            // is read from the workspace is always older than the rows still waiting in LDS.
             // The new entry takes over the LDS slot of the one kRingS places back, so an insertion that
             // reaches that far reads the workspace copy.
             auto put = [&](T wx, int32_t wi, int run_from) {
-                const int rows_done = w & ~3;
+                const int rows_done = fW;
                 int at = w;
                 const bool in_order = !(lastWi > wi);                         // the usual case: nothing to move, nothing to read
                 for (;;) {
@@ -220,16 +212,6 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 if (at < rows_done) myI[at] = wi;
                 if (at == w) lastWi = wi;                                     // index of the last entry written
                 ++w; ++wtot;
-                if ((w & 3) == 0) {
-                    T rx4[4]; int32_t ri4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int rr = ((segBase + w - 4 + j) & M) * kWave + lane;
-                        rx4[j] = ringX[rr]; ri4[j] = ringI[rr];
-                    }
-                    __builtin_memcpy(myX + w - 4, rx4, 32);
-                    __builtin_memcpy(myI + w - 4, ri4, 16);
-                }
             };
             // ---- stream entry (tc, snd): keep the largest index of the running value back
             T wx = 0; int32_t wi = 0; bool wr = false;
@@ -247,7 +229,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             if (ns == 0 || !(tr == lastBx)) brun = ns;
             lastBx = tr;
             {
-                const int rows_done = ns & ~3;
+                const int rows_done = fB;
                 int at = ns;
                 const int ib = bpos - segBase;
                 const int lo = brun > ib ? brun : ib;
@@ -263,12 +245,6 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = rcv;
                 if (at < rows_done) bufB[at] = rcv;
                 if (at == ns) lastBi = rcv;                                   // receiver of the last B entry
-                if (((ns + 1) & 3) == 0) {
-                    int32_t rb4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) rb4[j] = ringB[((segBase + ns - 3 + j) & M) * kWave + lane];
-                    __builtin_memcpy(bufB + ns - 3, rb4, 16);
-                }
             }
             // ---- consume
             const int dA = (x ? 1 : 0) + (y ? 1 : 0);
@@ -280,11 +256,21 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 // the root's final state: the largest value, in front of entries of the same value
                 if (!(tr == lastS)) runStart = w;
                 put(tr, 0, runStart);
-                for (int j = w & ~3; j < w; ++j) {                            // the last row of the stream if it is not complete
+                // everything of the segment that still waits in LDS
+                for (int j = fW; j < w; ++j) {
                     const int rr = ((segBase + j) & M) * kWave + lane;
                     myX[j] = ringX[rr]; myI[j] = ringI[rr];
                 }
-                for (int j = (n1 - 1) & ~3; j < n1; ++j) bufB[j] = ringB[((segBase + j) & M) * kWave + lane];
+                for (int j = fB; j < n1; ++j) bufB[j] = ringB[((segBase + j) & M) * kWave + lane];
+                for (int j = fO; j < n1; ++j) {
+                    const int slot = lane * kStage + (j & (kStage - 1));
+                    const int64_t oj = out_base + static_cast<int64_t>(k) * n1 + j;
+                    if (sched.src) sched.src[oj] = stS[slot];
+                    if (sched.dst) sched.dst[oj] = stD[slot];
+                    if (sched.seg) sched.seg[oj] = k;
+                    if (sched.tstart) static_cast<T *>(sched.tstart)[oj] = stT[slot];
+                }
+                fW = fB = fO = 0;
                 if (k == q - 1 && sched.T_greedy) static_cast<T *>(sched.T_greedy)[ci] = tr;
                 k += G; par ^= 1;
                 segBase = wtot; ns = 0; runStart = 0; brun = 0; bpos = wtot;
@@ -293,6 +279,42 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
                 apar = gl == 0 ? par ^ 1 : par;
                 apos = astart;
                 cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
+            }
+        }
+        // ---------------------------------------------------------------- full rows leave LDS (every fourth iteration)
+        if ((++iter & 3) == 0) {
+            T *const myX = bufX(lane, par);
+            int32_t *const myI = bufI(lane, par);
+            const int w = wtot - segBase;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                if (have && k < q && fW + 4 <= w) {
+                    T rx4[4]; int32_t ri4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int rr = ((segBase + fW + j) & M) * kWave + lane;
+                        rx4[j] = ringX[rr]; ri4[j] = ringI[rr];
+                    }
+                    __builtin_memcpy(myX + fW, rx4, 32);
+                    __builtin_memcpy(myI + fW, ri4, 16);
+                    fW += 4;
+                }
+                if (have && k < q && fB + 4 <= ns) {
+                    int32_t rb4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) rb4[j] = ringB[((segBase + fB + j) & M) * kWave + lane];
+                    __builtin_memcpy(bufB + fB, rb4, 16);
+                    fB += 4;
+                }
+                if (have && k < q && fO + 4 <= ns) {
+                    const int row = lane * kStage + (fO & (kStage - 1));
+                    const int64_t o4 = out_base + static_cast<int64_t>(k) * n1 + fO;
+                    if (sched.src) __builtin_memcpy(sched.src + o4, stS + row, 16);
+                    if (sched.dst) __builtin_memcpy(sched.dst + o4, stD + row, 16);
+                    if (sched.seg) { const int32_t kk[4] = {k, k, k, k}; __builtin_memcpy(sched.seg + o4, kk, 16); }
+                    if (sched.tstart) __builtin_memcpy(static_cast<T *>(sched.tstart) + o4, stT + row, 32);
+                    fO += 4;
+                }
             }
         }
         const bool on = have && k < q;
