@@ -64,13 +64,16 @@ __global__ void replay_store_offsets(OffsetChunk chunk, int base, int count, int
     if (i < count) dst[base + i] = chunk.v[i];
 }
 
-// One block per segment: tree of the segment's pairs -> linear program.
+// One block per segment: tree of the segment's pairs -> linear program.  The eight work arrays of p entries
+// sit in LDS when they fit (kLds), else in the workspace.
+template <bool kLds>
 __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t q, const int32_t *src, const int32_t *dst,
                                                               const int32_t *seg, int64_t n_pairs, uint32_t *prog,
                                                               int32_t *tmp, int32_t *flags)
 {
+    PRS_DYNAMIC_LDS(lds_raw);
     const int k = blockIdx.x, tid = threadIdx.x;
-    int32_t *base = tmp + static_cast<size_t>(k) * 8 * p;
+    int32_t *base = kLds ? reinterpret_cast<int32_t *>(lds_raw) : tmp + static_cast<size_t>(k) * 8 * p;
     int32_t *parent = base, *ord = base + p, *ci = base + 2 * p, *nchild = base + 3 * p, *size = base + 4 * p,
             *offStart = base + 5 * p, *fchild = base + 6 * p, *start = base + 7 * p;
     __shared__ int s_bad, s_count;
@@ -344,8 +347,13 @@ hipError_t launch_replay(const ReplayLaunch &L)
         hipLaunchKernelGGL(replay_store_offsets, dim3(1), dim3(kOffsetChunk), 0, L.stream, chunk, base, count, w.offsets);
     }
     hipLaunchKernelGGL(replay_clear_flags, dim3(1), dim3(64), 0, L.stream, w.flags);
-    hipLaunchKernelGGL(replay_build, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), 0, L.stream, L.p, L.q, L.src, L.dst,
-                       L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
+    const size_t build_lds = static_cast<size_t>(L.p) * 8 * 4;
+    if (build_lds <= 48 * 1024)
+        hipLaunchKernelGGL(replay_build<true>, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), build_lds, L.stream, L.p, L.q,
+                           L.src, L.dst, L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
+    else
+        hipLaunchKernelGGL(replay_build<false>, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), 0, L.stream, L.p, L.q,
+                           L.src, L.dst, L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     err = L.dtype == PRS_F32 ? launch_replay_t<float>(L, w, max_len, vec_ok) : launch_replay_t<int32_t>(L, w, max_len, vec_ok);
     if (err != hipSuccess) return err;
