@@ -44,7 +44,7 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
 {
     constexpr int M = kRing - 1;
     const int lane = lane_id(), gl = lane & (G - 1), gbase = lane & ~(G - 1);
-    const int prod = gbase | ((gl + G - 1) & (G - 1)), cons = gbase | ((gl + 1) & (G - 1));
+    const int prod = gbase | ((gl + G - 1) & (G - 1));
     const uint64_t gmask = (G == 64 ? ~UINT64_C(0) : ((UINT64_C(1) << G) - 1)) << gbase;
     T *mybuf = slot + static_cast<size_t>(lane) * 2 * slot_p;       // [2][slot_p]
     const T *prodbuf = slot + static_cast<size_t>(prod) * 2 * slot_p;
@@ -102,12 +102,11 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
         const bool active = have && k < q;
 
         // ---------------------------------------------------------------- what the neighbours have done so far
-        int pw = wtot, cpos = apos;
+        int pw = wtot;
         T plast = lastS;
         if (G > 1) {
             pw = __shfl(wtot, prod, kWave);
             plast = __shfl(lastS, prod, kWave);
-            cpos = __shfl(apos, cons, kWave);
         }
         const bool first = k == 0;
         const int aend = astart + p;
@@ -136,8 +135,10 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
         const bool y = u <= v;
         const T e2 = y ? u : v;
         const int dA = (x ? 1 : 0) + (y ? 1 : 0);
-        // my buffer `par` held the stream of two rounds ago: its reader must be through with it
-        const bool ok = active && e2 < kInf && e2 <= front && cpos >= segBase - p;
+        // (My buffer `par` held my stream of two rounds ago.  Its reader is through with it: I can only have
+        // finished the round in between after the first lane of the group finished it, and every lane after the
+        // first had to read its producer's whole stream to finish.)
+        const bool ok = active && e2 < kInf && e2 <= front;
 
         // ---------------------------------------------------------------- new state of the lane
         const T tc = wrap_add<T>(e2, cc), tr = wrap_add<T>(tc, gg);           // sender leaves at tc, receiver stays until tr
