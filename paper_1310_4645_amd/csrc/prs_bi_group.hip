@@ -39,31 +39,61 @@ size_t bi_group_lds_bytes(int lpc)
     return static_cast<size_t>(bi_group_capacity(lpc)) * (64 * 16 + (64 / lpc) * 16 * (lpc == 1 ? 1 : 2));
 }
 
+// Sums, minima and prefix sums over the 4 or 16 lanes of a group use data-parallel-primitive moves (a lane
+// reads its source operand from another lane of its row of 16: quad_perm inside a quad, row_ror/row_shr inside
+// the row) instead of LDS permutes: a group is a quad or a whole row, and these reductions sit on the dependent
+// path of every visit, a dozen of them.
+template <int CTRL> __device__ __forceinline__ int dpp_move(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);        // lanes without a source read 0
+}
+constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E;                          // quad_perm:[1,0,3,2], [2,3,0,1]
+constexpr int kQuadLane0 = 0x00, kQuadLane1 = 0x55, kQuadLane2 = 0xAA;     // quad_perm broadcasts of lane 0, 1, 2
+constexpr int kRowRor = 0x120, kRowShr = 0x110;                            // + distance 1..15
+
 template <int LPC> __device__ __forceinline__ int group_sum(int v)
 {
-#pragma unroll
-    for (int o = LPC / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, LPC);
+    if (LPC == 4) {
+        v += dpp_move<kQuadXor1>(v);
+        v += dpp_move<kQuadXor2>(v);
+    } else if (LPC == 16) {
+        v += dpp_move<kRowRor + 8>(v);
+        v += dpp_move<kRowRor + 4>(v);
+        v += dpp_move<kRowRor + 2>(v);
+        v += dpp_move<kRowRor + 1>(v);
+    }
     return v;
 }
 
 // exclusive prefix sum over the LPC lanes of a group
 template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, int gl)
 {
-    int inc = v;
-#pragma unroll
-    for (int o = 1; o < LPC; o <<= 1) {
-        const int u = __shfl_up(inc, o, LPC);
-        if (gl >= o) inc += u;
+    if (LPC == 4) {
+        const int a0 = dpp_move<kQuadLane0>(v), a1 = dpp_move<kQuadLane1>(v), a2 = dpp_move<kQuadLane2>(v);
+        return gl == 0 ? 0 : (gl == 1 ? a0 : (gl == 2 ? a0 + a1 : a0 + a1 + a2));
     }
-    return inc - v;
+    if (LPC == 16) {
+        int inc = v;
+        inc += dpp_move<kRowShr + 1>(inc);
+        inc += dpp_move<kRowShr + 2>(inc);
+        inc += dpp_move<kRowShr + 4>(inc);
+        inc += dpp_move<kRowShr + 8>(inc);
+        return inc - v;
+    }
+    (void)gl;
+    return 0;
 }
 
 template <int LPC> __device__ __forceinline__ int group_min(int v)
 {
-#pragma unroll
-    for (int o = LPC / 2; o > 0; o >>= 1) {
-        const int u = __shfl_xor(v, o, LPC);
-        v = u < v ? u : v;
+    if (LPC == 4) {
+        int u = dpp_move<kQuadXor1>(v); v = u < v ? u : v;
+        u = dpp_move<kQuadXor2>(v); v = u < v ? u : v;
+    } else if (LPC == 16) {
+        int u = dpp_move<kRowRor + 8>(v); v = u < v ? u : v;
+        u = dpp_move<kRowRor + 4>(v); v = u < v ? u : v;
+        u = dpp_move<kRowRor + 2>(v); v = u < v ? u : v;
+        u = dpp_move<kRowRor + 1>(v); v = u < v ? u : v;
     }
     return v;
 }
@@ -366,7 +396,12 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         }
                     }
                     if (gl < W && (l > 0 || j > jhi)) myrows[static_cast<size_t>(j) * LPC + gl] = row;
-                    if (j > jhi) jhi = j;
+                    if (j > jhi) {
+                        // a jump to the last segment can pass segments nobody has visited: their rows are empty
+                        for (int jj = jhi + 1; jj < j; ++jj)
+                            if (gl < W) myrows[static_cast<size_t>(jj) * LPC + gl] = 0;
+                        jhi = j;
+                    }
                     ++j;
                     // nobody paired and no candidate had already sent j
                     idle_visit = l == 0 && group_sum<LPC>(((sfree | rfree) & ~comp & row) != 0 ? 1 : 0) == 0;
