@@ -225,6 +225,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             T tn = t;
             if (events > 0) {
                 tn = minNew;
+#pragma unroll 4
                 for (int s = 0; s < ng; ++s) {
                     const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
                     if (se > t && se < tn) tn = se;
@@ -239,6 +240,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0;
             int keep = 0;
             const int nxt = kBufs == 1 ? 0 : cur ^ 1;
+#pragma unroll 4
             for (int s = 0; s < ng; ++s) {
                 const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
                 const uint64_t sm = gSm[s * kWave + lane], rm = gRm[s * kWave + lane];
@@ -354,15 +356,19 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         const T tc = t + cj, tr = tc + gj;
                         if (!(tc > t)) status = PRS_CFG_STALLED;
                         if (kSched) {                                     // e-th sender pairs with e-th receiver
+                            // segment and start time are the same for all pairs of the visit: the lanes of the
+                            // group write them side by side
+                            for (int e = gl; e < l; e += LPC) {
+                                const int64_t o = out_base + emitted + e;
+                                if (sched.seg) sched.seg[o] = j;
+                                if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                            }
                             uint64_t m = sset;
                             int e = exS;
                             while (m) {
                                 const int b = __builtin_ctzll(m);
                                 m &= m - 1;
-                                const int64_t o = out_base + emitted + e;
-                                if (sched.src) sched.src[o] = gl * 64 + b;
-                                if (sched.seg) sched.seg[o] = j;
-                                if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                                if (sched.src) sched.src[out_base + emitted + e] = gl * 64 + b;
                                 ++e;
                             }
                             m = rset;
