@@ -53,7 +53,8 @@ typedef enum {
     PRS_CFG_TOO_LARGE = 2,   /* p > p_max, q_req > q_max, or the schedule does not fit pair_capacity */
     PRS_CFG_STALLED = 3      /* time could not advance (a cost vanished against the clock in rounding) */
 } prs_cfg_status;
-typedef enum { PRS_CALL_SIMULATE = 0, PRS_CALL_SCHEDULE = 1, PRS_CALL_REPLAY = 2, PRS_CALL_OFFSETS = 3, PRS_CALL_SEARCH = 4 } prs_call;
+typedef enum { PRS_CALL_SIMULATE = 0, PRS_CALL_SCHEDULE = 1, PRS_CALL_REPLAY = 2, PRS_CALL_OFFSETS = 3, PRS_CALL_SEARCH = 4,
+               PRS_CALL_UNEQUAL = 5 } prs_call;
 
 /* A batch of n configurations, structure of arrays, DEVICE pointers.
  * q_req is the requested number of segments: the segment size is
@@ -87,7 +88,8 @@ typedef struct prs_times {
 
 /* Bytes of device scratch the given call needs for a batch of n
  * configurations with p <= p_max and q_req <= q_max (for PRS_CALL_REPLAY:
- * n = 1, p_max = p, q_max = q).  Host function, no GPU work. */
+ * n = 1, p_max = p, q_max = q; for PRS_CALL_UNEQUAL: q_max = m_max).  Host
+ * function, no GPU work. */
 size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_max, int32_t q_max);
 
 /*
@@ -180,6 +182,39 @@ typedef struct prs_best {
 int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int cost,
                                int32_t p_max, int32_t q_max, const prs_best *out,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Result columns of unequal_segmentation_batch, DEVICE pointers, any of them
+ * may be NULL.  T_* have the cost type of the call. */
+typedef struct prs_unequal {
+    void *T_all;            /* n * 2^(m_max-1): time of problem i under cut pattern c at [i * 2^(m_max-1) + c]
+                               (the "bad" value -1 / NaN where c is no segmentation of the problem's m) */
+    void *T_best;           /* n: smallest time over all 2^(m-1) segmentations */
+    uint32_t *cuts_best;    /* n: the numerically smallest cut pattern that reaches it */
+    int32_t *n_best;        /* n: how many segmentations reach it */
+    void *T_equi;           /* n: smallest time over the equi-segmentations, sizes ceil(m/k), k = 1..m */
+    uint32_t *cuts_equi;    /* n: the numerically smallest cut pattern among those */
+    int32_t *equi_optimal;  /* n: bit 0: T_equi == T_best; bit 1: an optimal segmentation has equal sizes
+                               except a smaller (or equal) last one, whatever that size */
+    int32_t *cfg_status;    /* n: prs_cfg_status of the problem */
+} prs_unequal;
+
+/*
+ * Unequal segmentation (Section 8: the message is fixed to a few units and
+ * every way of cutting it into consecutive segments is run through the
+ * unidirectional greedy algorithm; "Ratio" = best equi-segmentation time /
+ * best time over all segmentations = T_equi / T_best).  Problem i is
+ * (p, m, alpha, beta, gamma)[i] with 1 <= m <= m_max <= 24 units; beta and
+ * gamma are per unit; cfg->q_req is not read and may be NULL.  A segmentation
+ * is a cut pattern of m-1 bits: bit b set = a segment ends after unit b+1, so
+ * pattern 0 is the unsegmented message and 2^(m-1)-1 is m unit segments; its
+ * segments cost tcomm = alpha + beta*size, tcomp = gamma*size each and run
+ * through Algorithm 1 in order.  Equi-segmentations are the ones
+ * simulate_completion_batch cuts from a segment count.
+ * n * 2^(m_max-1) < 2^31.  Errors as simulate_completion_batch; workspace from
+ * prs_workspace_bytes(PRS_CALL_UNEQUAL, PRS_UNI, cost, n, p_max, m_max).
+ */
+int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t m_max,
+                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Version of the ABI, bumped on any incompatible change. */
 int prs_abi_version(void);

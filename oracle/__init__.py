@@ -267,3 +267,40 @@ def optimal_segmentation(cfgs, model, q_max, mode=MODE_EVENT | MODE_PRUNE):
         out["T_" + a] = best_T[a]
         out["q_" + a] = best_q[a]
     return out
+
+
+def compositions(m: int):
+    """The 2^(m-1) ways of cutting m units into consecutive segments, indexed by cut pattern: bit b of the
+    index set = a segment ends after unit b+1.  Index 0 is (m,), index 2^(m-1)-1 is (1, ..., 1)."""
+    out = []
+    for cuts in range(1 << (m - 1)):
+        parts, cur = [], 1
+        for b in range(m - 1):
+            if cuts >> b & 1:
+                parts.append(cur)
+                cur = 1
+            else:
+                cur += 1
+        parts.append(cur)
+        out.append(tuple(parts))
+    return out
+
+
+def unequal_segmentation(p, m, alpha, beta, gamma, cost="i64"):
+    """Section 8: the message is m units long and every segmentation of it is run through uni-greedy, one
+    after the other.  Returns dict(T_all, T_best, cuts_best, n_best, T_equi, cuts_equi, equi_optimal):
+    T_best the smallest time, cuts_best the smallest cut pattern reaching it, n_best how many do; T_equi /
+    cuts_equi the same over the equi-segmentations (those Section 2 cuts from a segment count 1..m);
+    equi_optimal bit 0: T_equi == T_best, bit 1: some optimal segmentation has equal sizes except a last
+    one that is not larger (the section's wording of "equi-segmentation")."""
+    comps = compositions(m)
+    T_all = [uni_greedy(p, list(c), alpha, beta, gamma, cost, want_schedule=False).T for c in comps]
+    T_best = min(T_all)
+    winners = [i for i, t in enumerate(T_all) if t == T_best]
+    by_count = {tuple(int(v) for v in equi_sizes(m, k)) for k in range(1, m + 1)}
+    equi = [i for i, c in enumerate(comps) if c in by_count]
+    T_equi = min(T_all[i] for i in equi)
+    cuts_equi = min(i for i in equi if T_all[i] == T_equi)
+    wide = any(all(x == comps[i][0] for x in comps[i][:-1]) and comps[i][-1] <= comps[i][0] for i in winners)
+    return dict(T_all=np.array(T_all), T_best=T_best, cuts_best=winners[0], n_best=len(winners), T_equi=T_equi,
+                cuts_equi=cuts_equi, equi_optimal=(1 if T_equi == T_best else 0) | (2 if wide else 0))

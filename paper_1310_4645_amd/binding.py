@@ -15,13 +15,13 @@ import numpy as np
 PRS_UNI, PRS_BI = 0, 1
 PRS_COST_I64, PRS_COST_F64 = 0, 1
 PRS_I32, PRS_F32 = 0, 1
-PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS, PRS_CALL_SEARCH = 0, 1, 2, 3, 4
+PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS, PRS_CALL_SEARCH, PRS_CALL_UNEQUAL = 0, 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("prs_abi_version", "prs_workspace_bytes", "simulate_completion_batch", "prs_pair_offsets",
-           "greedy_schedule_batch", "replay_reduction", "optimal_segmentation_batch")
+           "greedy_schedule_batch", "replay_reduction", "optimal_segmentation_batch", "unequal_segmentation_batch")
 
 
 class PrsError(RuntimeError):
@@ -41,6 +41,11 @@ class _Times(C.Structure):
 class _Best(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("T_greedy", "T_pipeline", "T_binary", "T_revopt", "q_greedy", "q_pipeline",
                                           "q_binary", "q_revopt", "cfg_status")]
+
+
+class _Unequal(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("T_all", "T_best", "cuts_best", "n_best", "T_equi", "cuts_equi",
+                                          "equi_optimal", "cfg_status")]
 
 
 def library_path() -> str:
@@ -76,6 +81,9 @@ def load_library():
         lib.optimal_segmentation_batch.restype = C.c_int
         lib.optimal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
                                                    C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.unequal_segmentation_batch.restype = C.c_int
+        lib.unequal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int32, C.c_int32,
+                                                   C.POINTER(_Unequal), C.c_void_p, C.c_size_t, C.c_void_p]
         _LIB = lib
     return _LIB
 
@@ -184,6 +192,30 @@ def optimal_segmentation_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max
     rc = lib.optimal_segmentation_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, C.byref(best),
                                         C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
     _check(rc, "optimal_segmentation_batch")
+    out["_workspace"] = ws
+    return out
+
+
+def unequal_segmentation_batch(cfg: DeviceConfigs, p_max: int, m_max: int, want_all=True, workspace=None):
+    """Every segmentation of cfg.m <= m_max units through uni-greedy.  Returns a dict of device tensors: T_all
+    (n x 2^(m_max-1), cost type, only if want_all), T_best, T_equi (cost type), cuts_best, cuts_equi (int32 holding
+    the cut patterns), n_best, equi_optimal, cfg_status (int32).  cfg.q_req is not read."""
+    import torch
+    lib = load_library()
+    n = len(cfg)
+    dev = cfg.p.device
+    tt = torch.int64 if cfg.cost == PRS_COST_I64 else torch.float64
+    out = {k: torch.empty(n, dtype=tt, device=dev) for k in ("T_best", "T_equi")}
+    out.update({k: torch.empty(n, dtype=torch.int32, device=dev)
+                for k in ("cuts_best", "n_best", "cuts_equi", "equi_optimal", "cfg_status")})
+    out["T_all"] = torch.empty((n, 1 << (m_max - 1)), dtype=tt, device=dev) if want_all else None
+    need = prs_workspace_bytes(PRS_CALL_UNEQUAL, PRS_UNI, cfg.cost, n, p_max, m_max)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    res = _Unequal(*[None if out[k] is None else out[k].data_ptr() for k, _ in _Unequal._fields_])
+    cs = cfg.struct()
+    rc = lib.unequal_segmentation_batch(C.byref(cs), n, cfg.cost, p_max, m_max, C.byref(res),
+                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+    _check(rc, "unequal_segmentation_batch")
     out["_workspace"] = ws
     return out
 

@@ -211,8 +211,10 @@ static bool bad_common(const prs_configs *cfg, int64_t n, int model, int cost, i
 }
 
 static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
-                      const TimesOut &times, const SchedOut &sched, void *workspace, size_t workspace_bytes, void *stream)
+                      const TimesOut &times, const SchedOut &sched, void *workspace, size_t workspace_bytes, void *stream,
+                      int32_t comp_m = 0)
 {
+    if (comp_m > 0 && (call != PRS_CALL_SIMULATE || model != PRS_UNI)) return PRS_EINVAL;   // compositions: uni-greedy times only
     if (n == 0) return PRS_OK;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
     const Layout lay = make_layout(call, model, n, p_max, q_max);
@@ -221,6 +223,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     PlanLaunch P;
     P.cfg = ConfigArrays{cfg->p, cfg->q_req, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
+    P.cfg.comp_m = comp_m;
     P.n = n; P.p_max = p_max; P.q_max = q_max; P.cost = cost;
     P.limits = lay.limits;
     P.header = reinterpret_cast<PlanHeader *>(ws + lay.header);
@@ -368,6 +371,119 @@ static SearchLayout make_search_layout(int model, int64_t n, int32_t p_max, int3
     return S;
 }
 
+// ---- every segmentation of a short message (Section 8) --------------------------------------------
+struct UnequalOut {
+    void *T_best; uint32_t *cuts_best; int32_t *n_best;
+    void *T_equi; uint32_t *cuts_equi; int32_t *equi_optimal; int32_t *cfg_status;
+};
+
+// Equal sizes except a last segment that may be smaller: returns that size, or 0 if the composition is not of this kind.
+__device__ __forceinline__ int equal_but_last(uint32_t comp)
+{
+    const int s = comp_first(comp);
+    comp >>= s;
+    while (comp != 0) {
+        const int z = comp_first(comp);
+        comp >>= z;
+        if (z != s && !(comp == 0 && z < s)) return 0;
+    }
+    return s;
+}
+
+constexpr int kPickThreads = 256;
+
+// One block per problem: minima over its 2^(m-1) times, ties to the smallest cut pattern.
+template <typename T>
+__global__ __launch_bounds__(kPickThreads) void unequal_pick(ConfigArrays in, int32_t p_max, int32_t m_max, const T *times,
+                                                             const int32_t *status, UnequalOut out)
+{
+    __shared__ T sBest[kPickThreads], sEqui[kPickThreads];
+    __shared__ uint32_t sBestC[kPickThreads], sEquiC[kPickThreads];
+    const int64_t i = blockIdx.x;
+    const int tid = static_cast<int>(threadIdx.x);
+    const int bits = m_max - 1;
+    const int64_t base = i << bits;
+    const int64_t m = in.m[i];
+    const int32_t st = status[base];                               // pattern 0 is a segmentation of every valid problem
+    if (st != PRS_CFG_OK) {
+        if (tid == 0) {
+            if (out.cfg_status) out.cfg_status[i] = st;
+            if (out.T_best) static_cast<T *>(out.T_best)[i] = CostTraits<T>::bad();
+            if (out.T_equi) static_cast<T *>(out.T_equi)[i] = CostTraits<T>::bad();
+            if (out.cuts_best) out.cuts_best[i] = 0;
+            if (out.cuts_equi) out.cuts_equi[i] = 0;
+            if (out.n_best) out.n_best[i] = 0;
+            if (out.equi_optimal) out.equi_optimal[i] = 0;
+        }
+        return;
+    }
+    const uint32_t n_comp = 1u << static_cast<int>(m - 1);
+    const uint32_t closing = 1u << static_cast<int>(m - 1);
+    const T kInf = CostTraits<T>::inf();
+    T best = kInf, equi = kInf;
+    uint32_t best_c = 0, equi_c = 0;
+    for (uint32_t c = tid; c < n_comp; c += kPickThreads) {        // rising patterns: the first minimum is the smallest pattern
+        const T v = times[base + c];
+        if (v < best) { best = v; best_c = c; }
+        const int s = equal_but_last(c | closing);
+        // an equi-segmentation cut from a count k has size ceil(m/k): s is such a size iff ceil(m / ceil(m/s)) == s
+        if (s > 0) {
+            const int64_t k = (m + s - 1) / s;
+            if ((m + k - 1) / k == s && v < equi) { equi = v; equi_c = c; }
+        }
+    }
+    sBest[tid] = best; sBestC[tid] = best_c; sEqui[tid] = equi; sEquiC[tid] = equi_c;
+    __syncthreads();
+    for (int t = 0; t < kPickThreads; ++t) {                        // every thread folds the whole table: all end with the same minima
+        const T b = sBest[t];
+        if (b < best || (b == best && sBestC[t] < best_c)) { best = b; best_c = sBestC[t]; }
+        const T e = sEqui[t];
+        if (e < equi || (e == equi && sEquiC[t] < equi_c)) { equi = e; equi_c = sEquiC[t]; }
+    }
+    // second pass: how many segmentations reach the minimum, and whether one of them has equal sizes but the last
+    int cnt = 0, wide = 0;
+    for (uint32_t c = tid; c < n_comp; c += kPickThreads) {
+        if (times[base + c] == best) {
+            ++cnt;
+            if (equal_but_last(c | closing) > 0) wide = 1;
+        }
+    }
+    __shared__ int sCnt[kPickThreads], sWide[kPickThreads];
+    sCnt[tid] = cnt; sWide[tid] = wide;
+    __syncthreads();
+    if (tid == 0) {
+        int total = 0, any_wide = 0;
+        for (int t = 0; t < kPickThreads; ++t) { total += sCnt[t]; any_wide |= sWide[t]; }
+        if (out.cfg_status) out.cfg_status[i] = PRS_CFG_OK;
+        if (out.T_best) static_cast<T *>(out.T_best)[i] = best;
+        if (out.cuts_best) out.cuts_best[i] = best_c;
+        if (out.n_best) out.n_best[i] = total;
+        if (out.T_equi) static_cast<T *>(out.T_equi)[i] = equi;
+        if (out.cuts_equi) out.cuts_equi[i] = equi_c;
+        if (out.equi_optimal) out.equi_optimal[i] = (equi == best ? 1 : 0) | (any_wide ? 2 : 0);
+    }
+}
+
+struct UnequalLayout {
+    int64_t n_exp;
+    size_t times, status, sim, total;
+};
+
+static UnequalLayout make_unequal_layout(int64_t n, int32_t p_max, int32_t m_max)
+{
+    UnequalLayout U;
+    U.n_exp = (n < 1 ? 1 : n) << (m_max - 1);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    U.times = take(static_cast<size_t>(U.n_exp) * 8);
+    U.status = take(static_cast<size_t>(U.n_exp) * 4);
+    U.sim = off;
+    U.total = off + make_layout(PRS_CALL_SIMULATE, PRS_UNI, U.n_exp, p_max, m_max).total;
+    return U;
+}
+
+constexpr int kUnequalMaxM = 24;
+
 }  // namespace prs
 
 using namespace prs;
@@ -383,6 +499,10 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
     if (call == PRS_CALL_REPLAY) return replay_workspace_bytes(p_max, q_max);
     if (call == PRS_CALL_OFFSETS) return kHeaderBytes;
     if (call == PRS_CALL_SEARCH) return make_search_layout(model, n, p_max, q_max).total;
+    if (call == PRS_CALL_UNEQUAL) {
+        if (q_max > kUnequalMaxM || (n << (q_max - 1)) >= (INT64_C(1) << 31)) return 0;
+        return make_unequal_layout(n, p_max, q_max).total;
+    }
     if (call != PRS_CALL_SIMULATE && call != PRS_CALL_SCHEDULE) return 0;
     return make_layout(call, model, n, p_max, q_max).total;
 }
@@ -444,6 +564,38 @@ int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int
                            reinterpret_cast<const double *>(ws + S.greedy), reinterpret_cast<const double *>(ws + S.pipeline),
                            reinterpret_cast<const double *>(ws + S.binary), reinterpret_cast<const double *>(ws + S.revopt),
                            reinterpret_cast<const int32_t *>(ws + S.status), b);
+    return hipGetLastError() == hipSuccess ? PRS_OK : PRS_EDEVICE;
+}
+
+int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t m_max,
+                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!cfg || !out || n < 0 || (cost != PRS_COST_I64 && cost != PRS_COST_F64) || p_max < 2 || p_max > (1 << 20) ||
+        m_max < 1 || m_max > kUnequalMaxM || (n << (m_max - 1)) >= (INT64_C(1) << 31))
+        return PRS_EINVAL;
+    if (n > 0 && (!cfg->p || !cfg->m || !cfg->alpha || !cfg->beta || !cfg->gamma)) return PRS_EINVAL;
+    if (n == 0) return PRS_OK;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
+    const UnequalLayout U = make_unequal_layout(n, p_max, m_max);
+    if (workspace_bytes < U.total) return PRS_ENOSPC;
+    char *ws = static_cast<char *>(workspace);
+    void *all = out->T_all ? out->T_all : static_cast<void *>(ws + U.times);
+    int32_t *status = reinterpret_cast<int32_t *>(ws + U.status);
+    const prs_configs problems{cfg->p, nullptr, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
+    TimesOut t{all, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, status};
+    SchedOut s{};
+    const int rc = run_greedy(PRS_CALL_SIMULATE, &problems, U.n_exp, PRS_UNI, cost, p_max, m_max, t, s, ws + U.sim,
+                              workspace_bytes - U.sim, stream, m_max);
+    if (rc != PRS_OK) return rc;
+    const ConfigArrays in{cfg->p, nullptr, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
+    const UnequalOut u{out->T_best, out->cuts_best, out->n_best, out->T_equi, out->cuts_equi, out->equi_optimal, out->cfg_status};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (cost == PRS_COST_I64)
+        hipLaunchKernelGGL((unequal_pick<int64_t>), dim3(static_cast<unsigned>(n)), dim3(kPickThreads), 0, st, in, p_max, m_max,
+                           static_cast<const int64_t *>(all), status, u);
+    else
+        hipLaunchKernelGGL((unequal_pick<double>), dim3(static_cast<unsigned>(n)), dim3(kPickThreads), 0, st, in, p_max, m_max,
+                           static_cast<const double *>(all), status, u);
     return hipGetLastError() == hipSuccess ? PRS_OK : PRS_EDEVICE;
 }
 

@@ -36,21 +36,62 @@ template <typename T> struct Config {
     int64_t m, sz, sz_last;
     T alpha, beta, gamma;
     T c_full, g_full, c_last, g_last;
+    uint32_t comp;         // composition mode: cut bits of the segmentation with a closing bit at position m-1 (else 0)
     int32_t status;
     __device__ __forceinline__ T c(int j) const { return j == q - 1 ? c_last : c_full; }
     __device__ __forceinline__ T g(int j) const { return j == q - 1 ? g_last : g_full; }
 };
 
+// comp_m = 0: configuration i is entry i of the arrays, cut into equal segments from q_req.
+// comp_m = M > 0 (Section 8, every segmentation of a short message): configuration i is problem i >> (M-1) of the
+// arrays cut by the bit pattern i & (2^(M-1) - 1): bit b set = a segment ends after unit b+1 of the problem's m units
+// (m <= M; patterns with bits at or above m-1 are no segmentation of that problem and are marked PRS_CFG_BAD_PARAM).
+// Only the uni-greedy completion-time kernel reads compositions.
 struct ConfigArrays {
     const int32_t *p, *q_req;
     const int64_t *m;
     const void *alpha, *beta, *gamma;
+    int32_t comp_m = 0;
 };
+
+// Size of the first segment of a composition (cut bits closed by the bit after the last unit) and the rest of it.
+__device__ __forceinline__ int comp_first(uint32_t comp) { return __builtin_ctz(comp) + 1; }
+__device__ __forceinline__ uint32_t comp_drop(uint32_t comp, int segments)
+{
+    for (int s = 0; s < segments && comp != 0; ++s) comp >>= comp_first(comp);
+    return comp;
+}
 
 template <typename T>
 __device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_t i, int32_t p_max, int32_t q_max)
 {
     Config<T> c;
+    c.comp = 0;
+    if (a.comp_m > 0) {
+        const int bits = a.comp_m - 1;
+        const uint32_t cuts = static_cast<uint32_t>(i & ((INT64_C(1) << bits) - 1));
+        i >>= bits;
+        c.p = a.p[i];
+        c.m = a.m[i];
+        c.alpha = static_cast<const T *>(a.alpha)[i];
+        c.beta = static_cast<const T *>(a.beta)[i];
+        c.gamma = static_cast<const T *>(a.gamma)[i];
+        c.status = PRS_CFG_OK;
+        c.q = 1; c.sz = 1; c.sz_last = 1;
+        c.c_full = c.g_full = c.c_last = c.g_last = 0;
+        if (c.p < 2 || c.m < 1 || c.m > a.comp_m || (cuts >> static_cast<int>(c.m - 1)) != 0 || !CostTraits<T>::valid(c.alpha) ||
+            !CostTraits<T>::valid(c.beta) || !CostTraits<T>::valid(c.gamma)) {
+            c.status = PRS_CFG_BAD_PARAM;
+            return c;
+        }
+        if (c.p > p_max || a.comp_m > q_max) { c.status = PRS_CFG_TOO_LARGE; return c; }
+        c.q = __builtin_popcount(cuts) + 1;
+        c.comp = cuts | (1u << static_cast<int>(c.m - 1));
+        // the smallest and the largest cost a segment of this problem can have (sizes 1 and m)
+        const T c1 = c.alpha + c.beta, cm = c.alpha + c.beta * static_cast<T>(c.m), gm = c.gamma * static_cast<T>(c.m);
+        if (!(c1 > 0) || !(cm > 0) || !CostTraits<T>::valid(cm) || !CostTraits<T>::valid(gm)) c.status = PRS_CFG_BAD_PARAM;
+        return c;
+    }
     c.p = a.p[i];
     const int32_t q_req = a.q_req[i];
     c.m = a.m[i];

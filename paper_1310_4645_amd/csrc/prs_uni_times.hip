@@ -37,7 +37,9 @@ constexpr int kNear = kRing - 5;   // entries this close behind the writer are r
 size_t uni_times_lds_bytes() { return static_cast<size_t>(kRing) * kWave * 8; }
 size_t uni_times_slot_bytes(int32_t p_cap) { return static_cast<size_t>(kWave) * 2 * static_cast<size_t>(p_cap) * 8; }
 
-template <typename T, int G>
+// kComp: the segments of a configuration have the sizes its composition gives (Section 8) instead of one size
+// and a smaller last one; every lane keeps the part of the composition that starts at its segment.
+template <typename T, int G, bool kComp>
 __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg, int32_t p_max, int32_t q_max, int model,
                                                const TimesOut &times, PlanHeader *plan, const int32_t *order, int cls, T *slot,
                                                int32_t slot_p)
@@ -56,6 +58,8 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
     int64_t ci = 0;
     int p = 2, q = 1;
     T c_full = 0, g_full = 0, c_last = 0, g_last = 0;
+    T alpha = 0, beta = 0, gamma = 0;   // kComp only
+    uint32_t rest = 0;                  // kComp only: the composition from my segment on (per lane)
     // ---- per-lane state.  Positions count the entries of a stream from the start of the configuration:
     // every finished segment adds p of them.
     int k = 0;                      // segment this lane is running (>= q: none left)
@@ -82,7 +86,7 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
                 ci = order[begin + ticket];
                 const Config<T> c = decode_config<T>(cfg, ci, p_max, q_max);
                 if (gl == 0) {
-                    write_closed_forms<T>(times, ci, c, model);
+                    if (!kComp) write_closed_forms<T>(times, ci, c, model);
                     if (times.cfg_status) times.cfg_status[ci] = c.status;
                     if (c.status != PRS_CFG_OK && times.greedy) static_cast<T *>(times.greedy)[ci] = CostTraits<T>::bad();
                 }
@@ -94,6 +98,13 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
                     wtot = segBase = apos = astart = bpos = 0;
                     lastS = 0; farA = farB = false;
                     cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
+                    if (kComp) {
+                        alpha = c.alpha; beta = c.beta; gamma = c.gamma;
+                        rest = comp_drop(c.comp, gl);
+                        const T sz = static_cast<T>(rest ? comp_first(rest) : 1);
+                        const T bs = beta * sz;                               // each product and sum rounded on its own
+                        cc = alpha + bs; gg = gamma * sz;
+                    }
                 }
             }
         }
@@ -159,6 +170,12 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
                 apar = gl == 0 ? par ^ 1 : par;
                 apos = astart;
                 cc = k == q - 1 ? c_last : c_full; gg = k == q - 1 ? g_last : g_full;
+                if (kComp) {
+                    rest = comp_drop(rest, G);
+                    const T sz = static_cast<T>(rest ? comp_first(rest) : 1);
+                    const T bs = beta * sz;
+                    cc = alpha + bs; gg = gamma * sz;
+                }
             }
         }
         const bool on = have && k < q;
@@ -201,7 +218,7 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
 // One launch for the whole batch: every wavefront works through the classes from the heaviest
 // configurations (largest groups) to the lightest, so the long-running ones start first and the light
 // ones fill the machine around them.
-template <typename T>
+template <typename T, bool kComp>
 __global__ __launch_bounds__(kWave) void uni_times_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model, TimesOut times,
                                                           PlanHeader *plan, const int32_t *order, char *slots, size_t slot_bytes,
                                                           int32_t slot_p)
@@ -209,23 +226,30 @@ __global__ __launch_bounds__(kWave) void uni_times_kernel(ConfigArrays cfg, int3
     PRS_DYNAMIC_LDS(lds_raw);
     T *ring = reinterpret_cast<T *>(lds_raw);                    // [kRing][64]
     T *slot = reinterpret_cast<T *>(slots + static_cast<size_t>(blockIdx.x) * slot_bytes);
-    uni_times_body<T, 32>(ring, cfg, p_max, q_max, model, times, plan, order, 3, slot, slot_p);
+    uni_times_body<T, 32, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 16>(ring, cfg, p_max, q_max, model, times, plan, order, 2, slot, slot_p);
+    uni_times_body<T, 16, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 2, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 4>(ring, cfg, p_max, q_max, model, times, plan, order, 1, slot, slot_p);
+    uni_times_body<T, 4, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 1, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 1>(ring, cfg, p_max, q_max, model, times, plan, order, 0, slot, slot_p);
+    uni_times_body<T, 1, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 0, slot, slot_p);
+}
+
+template <typename T, bool kComp>
+static void launch_uni_times_as(const UniLaunch &L)
+{
+    hipLaunchKernelGGL((uni_times_kernel<T, kComp>), dim3(L.grid), dim3(kWave), uni_times_lds_bytes(), L.stream, L.cfg, L.p_max,
+                       L.q_max, L.model, L.times, L.plan, L.order, L.slots, L.slot_bytes, L.slot_p);
 }
 
 hipError_t launch_uni_times(const UniLaunch &L)
 {
-    if (L.cost == PRS_COST_I64)
-        hipLaunchKernelGGL((uni_times_kernel<int64_t>), dim3(L.grid), dim3(kWave), uni_times_lds_bytes(), L.stream, L.cfg, L.p_max,
-                           L.q_max, L.model, L.times, L.plan, L.order, L.slots, L.slot_bytes, L.slot_p);
-    else
-        hipLaunchKernelGGL((uni_times_kernel<double>), dim3(L.grid), dim3(kWave), uni_times_lds_bytes(), L.stream, L.cfg, L.p_max,
-                           L.q_max, L.model, L.times, L.plan, L.order, L.slots, L.slot_bytes, L.slot_p);
+    const bool comp = L.cfg.comp_m > 0;
+    if (L.cost == PRS_COST_I64) {
+        if (comp) launch_uni_times_as<int64_t, true>(L); else launch_uni_times_as<int64_t, false>(L);
+    } else {
+        if (comp) launch_uni_times_as<double, true>(L); else launch_uni_times_as<double, false>(L);
+    }
     return hipGetLastError();
 }
 

@@ -324,6 +324,106 @@ def test_optimal_segmentation_matches_trying_each_count(prs, model, cost):
     assert st[2] == 1 and np.all(st[ok] == 0) and _np(got["q_greedy"])[2] == -1
 
 
+# --------------------------------------------------------------------------- unequal segmentation (Section 8)
+_SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
+
+
+@pytest.mark.parametrize("limits", [None, "0,0,0", "0,0,1000000000", "0,1000000000,1000000000"])
+@pytest.mark.parametrize("cost", ["i64", "f64"])
+def test_unequal_segmentation_matches_the_oracle(prs, cost, limits, monkeypatch):
+    """Every segmentation of short messages of mixed length through uni-greedy, at every group size: all
+    2^(m-1) times and the per-problem summary against the oracle running the segmentations one by one."""
+    if limits is not None:
+        monkeypatch.setenv("PRS_UNI_GROUP_WORK", limits)
+    rng = np.random.default_rng(808)
+    n = 36
+    p = rng.integers(2, 70, n).astype(np.int32)
+    m = rng.integers(1, 10, n).astype(np.int64)
+    p[:4] = [2, 3, 64, 65]; m[:4] = [9, 1, 9, 2]
+    if cost == "i64":
+        al, be, ga = (rng.integers(0, 12, n).astype(np.int64), rng.integers(1, 3, n).astype(np.int64),
+                      rng.integers(0, 3, n).astype(np.int64))
+    else:
+        al, be, ga = 10.0 ** rng.uniform(-6, -5, n), 10.0 ** rng.uniform(-7, -5, n), 10.0 ** rng.uniform(-7, -5, n)
+        al[5:9] = 1.0; be[5:9] = 0.0; ga[5:9] = 2.0 ** -52              # sums that collide in rounding
+    p[4] = 1                                                            # not a valid problem
+    m[9] = 12                                                           # longer than m_max
+    host = prs_inputs.SweepConfigs(p, np.zeros(n, np.int32), m, al, be, ga, cost)
+    dev = prs.DeviceConfigs.from_host(host)
+    m_max = 9
+    got = prs.unequal_segmentation_batch(dev, 70, m_max)
+    _sync()
+    st = _np(got["cfg_status"])
+    T_all = _np(got["T_all"])
+    for i in range(n):
+        if i in (4, 9):
+            assert st[i] == 1 and _np(got["n_best"])[i] == 0
+            assert np.all(T_all[i] == -1) if cost == "i64" else np.all(np.isnan(T_all[i]))
+            continue
+        assert st[i] == 0
+        ref = O.unequal_segmentation(int(p[i]), int(m[i]), al[i].item(), be[i].item(), ga[i].item(), cost)
+        nc = 1 << (int(m[i]) - 1)
+        assert np.array_equal(T_all[i, :nc], ref["T_all"]), i
+        assert np.all(T_all[i, nc:] == -1) if cost == "i64" else np.all(np.isnan(T_all[i, nc:]))
+        for key in _SUMMARY:
+            assert _np(got[key])[i].item() == ref[key], (i, key)
+
+
+def test_unequal_segmentation_reproduces_table4(prs):
+    """The paper's experiment at full size (m = 10, beta = 1, 29 values of alpha, gamma in {0, 1}, 17 values of
+    p up to 1024: 986 problems x 512 segmentations) on the GPU, checked against the printed table: the same 61
+    problems are optimised only by unequal segmentations, with the printed optimal sets, best
+    equi-segmentations and ratios, a largest gain of 7.3 % and a mean gain of 2.0 %."""
+    import os
+    alphas = list(range(0, 11)) + list(range(20, 101, 10)) + list(range(200, 1001, 100))
+    ps = sorted([2 ** k for k in range(2, 11)] + [3 * 2 ** k for k in range(1, 9)])
+    probs = [(p, a, g) for p in ps for a in alphas for g in (0, 1)]
+    assert len(probs) == 986
+    n = len(probs)
+    host = prs_inputs.SweepConfigs(np.array([x[0] for x in probs], np.int32), np.zeros(n, np.int32), np.full(n, 10, np.int64),
+                                   np.array([x[1] for x in probs], np.int64), np.ones(n, np.int64),
+                                   np.array([x[2] for x in probs], np.int64), "i64")
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.unequal_segmentation_batch(dev, 1024, 10)
+    _sync()
+    assert np.all(_np(got["cfg_status"]) == 0)
+    T_all, T_best, T_equi = _np(got["T_all"]), _np(got["T_best"]), _np(got["T_equi"])
+    flags, n_best, cuts_equi = _np(got["equi_optimal"]), _np(got["n_best"]), _np(got["cuts_equi"])
+    comps = O.compositions(10)
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table4_unequal_segmentation.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            p, a, g, ratio, equi, opt = line.split()
+            rows[(int(p), int(a), int(g))] = (ratio, tuple(map(int, equi.split(","))),
+                                              sorted(tuple(map(int, s.split(","))) for s in opt.split(";")))
+    unequal_only = [i for i in range(n) if not flags[i] & 2]
+    assert sorted(probs[i] for i in unequal_only) == sorted(rows)
+    gains = []
+    for i in unequal_only:
+        ratio, equi, opt = rows[probs[i]]
+        assert f"{T_equi[i] / T_best[i]:.4f}" == ratio
+        assert sorted(comps[c] for c in np.nonzero(T_all[i] == T_best[i])[0]) == opt and n_best[i] == len(opt)
+        assert T_all[i, comps.index(equi)] == T_equi[i] and comps.index(equi) >= cuts_equi[i]
+        gains.append(T_equi[i] / T_best[i] - 1.0)
+    assert f"{max(gains) * 100:.1f}" == "7.3" and f"{sum(gains) / len(gains) * 100:.1f}" == "2.0"
+    # where an equi-segmentation is optimal in the section's wider sense, the ones cut from a count may still lose
+    assert np.all(T_equi >= T_best) and np.all((flags & 1) == (T_equi == T_best))
+    # sampled problems element by element against the oracle
+    for i in (0, 57, 200, 333, 640):
+        p, a, g = probs[i]
+        if p > 96:
+            continue
+        ref = O.unequal_segmentation(p, 10, a, 1, g)
+        assert np.array_equal(T_all[i], ref["T_all"])
+    big = [i for i in range(n) if probs[i][0] == 1024][:2]
+    for i in big:                                                       # two of the largest, a few segmentations each
+        p, a, g = probs[i]
+        for c in (0, 1, 255, 300, 511):
+            assert T_all[i, c] == O.uni_greedy(p, list(comps[c]), a, 1, g, want_schedule=False).T
+
+
 # --------------------------------------------------------------------------- replay
 def _replay_case(prs, p, sizes, model, seg_off, dtype, cost=("i64", 2, 1, 1), strided=False):
     import torch

@@ -227,6 +227,31 @@ def test_table4_unequal_segmentation_rows():
     assert f"{sum(gains) / len(gains) * 100:.1f}" == "2.0"    # "average improvement was 2.0%"
 
 
+def test_unequal_segmentation_summary_matches_table4_rows():
+    """Section 8 / Table IV through oracle.unequal_segmentation (the per-problem summary the GPU entry point
+    also returns): for printed rows the ratio, the best equi-segmentation, the number of optimal
+    segmentations and the first of them in cut-pattern order are the printed ones and no kind of
+    equi-segmentation is optimal; an experiment the table does not list has ratio 1."""
+    comps = O.compositions(10)
+    assert len(comps) == 512 and comps[0] == (10,) and comps[511] == (1,) * 10 and comps[1] == (1, 9)
+    rows = [r for r in _table4_rows() if r[0] <= 48]
+    assert len(rows) >= 12
+    for p, a, g, ratio, equi_printed, opt_printed in rows:
+        r = O.unequal_segmentation(p, 10, a, 1, g)
+        assert f"{r['T_equi'] / r['T_best']:.4f}" == ratio
+        assert r["n_best"] == len(opt_printed) and comps[r["cuts_best"]] in opt_printed
+        assert r["cuts_best"] == min(comps.index(c) for c in opt_printed)
+        assert r["T_all"][comps.index(equi_printed)] == r["T_equi"] and r["equi_optimal"] == 0
+    listed = {(p, a, g) for p, a, g, *_ in _table4_rows()}
+    for p, a, g in [(4, 5, 0), (6, 20, 1), (8, 100, 0), (16, 1000, 1)]:
+        assert (p, a, g) not in listed
+        r = O.unequal_segmentation(p, 10, a, 1, g)
+        assert r["T_equi"] == r["T_best"] and r["equi_optimal"] == 3
+    # one unit: a single segmentation, which is the equi one
+    r = O.unequal_segmentation(5, 1, 2, 1, 1)
+    assert (r["n_best"], r["cuts_best"], r["equi_optimal"]) == (1, 0, 3) and r["T_best"] == 3 * (2 + 1 + 1)
+
+
 def test_pipeline_is_optimised_by_equal_segments():
     # Section 8: "For the pipeline algorithm, all experiments were optimized by equi-segmentation"
     comps = list(_compositions(10))
