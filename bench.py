@@ -233,6 +233,37 @@ def main():
         del wsb
     out["optimal_segmentation"] = {"problems": SEARCH_PROBLEMS, "candidates_per_problem": int(np.log2(Q_MAX)) + 1,
                                    "ms": search_ms, "note": "not part of the step or of value"}
+    # outside the timed step as well: the unequal-segmentation experiment of Section 8 at the paper's size (986 problems,
+    # m = 10: 512 segmentations each) and with a longer message (m = 14: 8192 each)
+    alphas = list(range(0, 11)) + list(range(20, 101, 10)) + list(range(200, 1001, 100))
+    ps = [2 ** k for k in range(2, 11)] + [3 * 2 ** k for k in range(1, 9)]
+    probs = [(p, a, g) for p in ps for a in alphas for g in (0, 1)]
+    uneq = {}
+    for m_units in (10, 14):
+        n_u = len(probs)
+        hu = prs_inputs.SweepConfigs(np.array([x[0] for x in probs], np.int32), np.zeros(n_u, np.int32),
+                                     np.full(n_u, m_units, np.int64), np.array([x[1] for x in probs], np.int64),
+                                     np.ones(n_u, np.int64), np.array([x[2] for x in probs], np.int64), "i64")
+        du = prs.DeviceConfigs.from_host(hu)
+        wsb = torch.empty(prs.prs_workspace_bytes(prs.PRS_CALL_UNEQUAL, prs.PRS_UNI, prs.PRS_COST_I64, n_u, P_MAX, m_units) + 256,
+                          dtype=torch.uint8, device="cuda")
+        res = prs.unequal_segmentation_batch(du, P_MAX, m_units, want_all=False, workspace=wsb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        res = prs.unequal_segmentation_batch(du, P_MAX, m_units, want_all=False, workspace=wsb)
+        e1.record()
+        torch.cuda.synchronize()
+        flags = res["equi_optimal"].cpu().numpy()
+        ratio = (res["T_equi"].double() / res["T_best"].double()).cpu().numpy()
+        only = (flags & 2) == 0
+        uneq[f"m{m_units}"] = {"problems": n_u, "segmentations_per_problem": 1 << (m_units - 1), "ms": e0.elapsed_time(e1),
+                               "optimised_only_by_unequal": int(only.sum()),
+                               "max_gain_pct": float((ratio[only].max() - 1) * 100) if only.any() else 0.0,
+                               "mean_gain_pct": float((ratio[only].mean() - 1) * 100) if only.any() else 0.0}
+        del wsb, res
+    uneq["note"] = "not part of the step or of value; m10 is the paper's experiment (61 problems, 7.3 %, 2.0 %)"
+    out["unequal_segmentation"] = uneq
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host)
     print(json.dumps(out))

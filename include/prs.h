@@ -46,7 +46,9 @@ extern "C" {
 typedef enum { PRS_OK = 0, PRS_EINVAL = 1, PRS_ENOSPC = 2, PRS_EDEVICE = 3 } prs_status;
 typedef enum { PRS_UNI = 0, PRS_BI = 1 } prs_model;      /* one port / separate send and receive ports (Section 2) */
 typedef enum { PRS_COST_I64 = 0, PRS_COST_F64 = 1 } prs_cost;
-typedef enum { PRS_I32 = 0, PRS_F32 = 1 } prs_dtype;
+typedef enum { PRS_I32 = 0, PRS_F32 = 1, PRS_F64 = 2, PRS_I64 = 3 } prs_dtype;
+/* combine operation of replay_reduction, OR-ed into its dtype argument */
+typedef enum { PRS_OP_SUM = 0, PRS_OP_MAX = 0x100 } prs_op;
 typedef enum {
     PRS_CFG_OK = 0,
     PRS_CFG_BAD_PARAM = 1,   /* p < 2, q_req < 1, m < 1, a negative or non-finite cost, or tcomm = 0 */
@@ -147,8 +149,13 @@ int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost
  * non-decreasing from 0 to n_elems; read before the call returns).
  * src, dst, seg: device, n_pairs = (p-1)q entries, in which every non-root
  * processor sends every segment exactly once, after all it receives of it.
- * dtype: PRS_I32 (wrapping add) or PRS_F32 (IEEE add, no FMA, denormals
- * kept).  status: device int32, receives 0, or 1 if the schedule is not a
+ * dtype: element type PRS_I32, PRS_I64 (wrapping add), PRS_F32 or PRS_F64
+ * (IEEE add, no FMA, denormals kept), optionally OR-ed with PRS_OP_MAX: the
+ * combine is then buf_dst = max(buf_dst, buf_src) instead of the sum (the
+ * paper's reduction is any associative and commutative operation; Section 1),
+ * floating point
+ * compared in the IEEE total order (-0 below +0, NaNs at the two ends), so
+ * that the result is a well-defined element of the inputs.  status: device int32, receives 0, or 1 if the schedule is not a
  * set of q in-trees on p processors, or 2 if a combine tree needs more
  * nested partial sums than the kernel holds (then out is not written).
  * Limits: 2 <= p <= 4096, q <= 65536, (p-1)q < 2^31.

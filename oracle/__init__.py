@@ -171,21 +171,43 @@ def exhaustive_uni(p, sizes, alpha, beta, gamma) -> int:
                                             C.c_int64(alpha), C.c_int64(beta), C.c_int64(gamma)))
 
 
-def replay(p, seg_elem_offset, src, dst, seg, buf: np.ndarray) -> np.ndarray:
-    """Replays the schedule on a copy of buf (p rows); returns row 0."""
+def total_order_key(x: np.ndarray) -> np.ndarray:
+    """IEEE total order of floating-point values as signed integers: the bit pattern read as sign and
+    magnitude (-NaN < -inf < ... < -0 < +0 < ... < +inf < +NaN)."""
+    it = np.int32 if x.dtype == np.float32 else np.int64
+    bits = x.view(it)
+    mag = it(np.iinfo(it).max)                                  # every bit but the sign
+    return np.where(bits < 0, bits ^ mag, bits)
+
+
+def replay(p, seg_elem_offset, src, dst, seg, buf: np.ndarray, op: str = "sum") -> np.ndarray:
+    """Section 4: the receiver of a pair combines the segment it received with its own.  Applies
+    buf[dst, segment] = buf[dst, segment] (+ or max) buf[src, segment] pair by pair, in the order given, on a
+    copy of buf (p rows); returns row 0.  int32 and float32 sums run in the C oracle; the other element
+    types and the maximum are the same loop with numpy's element-wise operations (wrapping integer add,
+    IEEE add, maximum in the IEEE total order for floating point)."""
     work = np.ascontiguousarray(buf).copy()
     assert work.shape[0] == p
     off = np.ascontiguousarray(seg_elem_offset, dtype=np.int64)
     src = np.ascontiguousarray(src, np.int32); dst = np.ascontiguousarray(dst, np.int32)
     seg = np.ascontiguousarray(seg, np.int32)
-    if work.dtype == np.int32:
-        fn, ct = lib().orc_replay_i32, C.c_int32
-    elif work.dtype == np.float32:
-        fn, ct = lib().orc_replay_f32, C.c_float
-    else:
-        raise TypeError(work.dtype)
-    fn(C.c_int32(p), C.c_int64(work.shape[1]), _ptr(off, C.c_int64), C.c_int64(src.shape[0]),
-       _ptr(src, C.c_int32), _ptr(dst, C.c_int32), _ptr(seg, C.c_int32), _ptr(work, ct))
+    if op == "sum" and work.dtype in (np.int32, np.float32):
+        fn, ct = (lib().orc_replay_i32, C.c_int32) if work.dtype == np.int32 else (lib().orc_replay_f32, C.c_float)
+        fn(C.c_int32(p), C.c_int64(work.shape[1]), _ptr(off, C.c_int64), C.c_int64(src.shape[0]),
+           _ptr(src, C.c_int32), _ptr(dst, C.c_int32), _ptr(seg, C.c_int32), _ptr(work, ct))
+        return work[0].copy()
+    if work.dtype not in (np.int32, np.int64, np.float32, np.float64) or op not in ("sum", "max"):
+        raise TypeError((work.dtype, op))
+    floating = work.dtype in (np.float32, np.float64)
+    with np.errstate(over="ignore", invalid="ignore"):
+        for s, d, k in zip(src.tolist(), dst.tolist(), seg.tolist()):
+            a, b = work[d, off[k]:off[k + 1]], work[s, off[k]:off[k + 1]]
+            if op == "sum":
+                a += b                                            # numpy integer addition wraps, floating point is IEEE
+            elif floating:
+                a[...] = np.where(total_order_key(a) < total_order_key(b), b, a)
+            else:
+                np.maximum(a, b, out=a)
     return work[0].copy()
 
 

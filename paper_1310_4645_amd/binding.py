@@ -14,7 +14,8 @@ import numpy as np
 
 PRS_UNI, PRS_BI = 0, 1
 PRS_COST_I64, PRS_COST_F64 = 0, 1
-PRS_I32, PRS_F32 = 0, 1
+PRS_I32, PRS_F32, PRS_F64, PRS_I64 = 0, 1, 2, 3
+PRS_OP_SUM, PRS_OP_MAX = 0, 0x100
 PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS, PRS_CALL_SEARCH, PRS_CALL_UNEQUAL = 0, 1, 2, 3, 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -257,15 +258,18 @@ def greedy_schedule_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int
     return {"src": src, "dst": dst, "seg": seg, "t_start": t_start, "T_greedy": T, "cfg_status": st, "_workspace": ws}
 
 
-def replay_reduction(p: int, q: int, seg_elem_offset, src, dst, seg, inp, out=None, workspace=None):
-    """inp: device tensor [p, n_elems] (int32 or float32, rows may be strided); seg_elem_offset: host int64
-    array of q+1 entries.  Returns (out, status) device tensors."""
+def replay_reduction(p: int, q: int, seg_elem_offset, src, dst, seg, inp, out=None, workspace=None, op=PRS_OP_SUM):
+    """inp: device tensor [p, n_elems] (int32, int64, float32 or float64, rows may be strided); seg_elem_offset:
+    host int64 array of q+1 entries; op: PRS_OP_SUM or PRS_OP_MAX.  Returns (out, status) device tensors."""
     import torch
     lib = load_library()
     off = np.ascontiguousarray(seg_elem_offset, dtype=np.int64)
     n_elems = int(inp.shape[1])
     assert inp.stride(1) == 1
-    dtype = PRS_F32 if inp.dtype == torch.float32 else PRS_I32
+    kinds = {torch.int32: PRS_I32, torch.float32: PRS_F32, torch.float64: PRS_F64, torch.int64: PRS_I64}
+    if inp.dtype not in kinds:
+        raise PrsError(f"replay_reduction: unsupported element type {inp.dtype}")
+    dtype = kinds[inp.dtype] | op
     if out is None:
         out = torch.empty(n_elems, dtype=inp.dtype, device=inp.device)
     status = torch.empty(1, dtype=torch.int32, device=inp.device)

@@ -626,14 +626,16 @@ int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset, const
 {
     if (p < 2 || p > 4096 || q < 1 || q > 65536 || !seg_elem_offset || !src || !dst || !seg || !in || !out) return PRS_EINVAL;
     if (n_pairs != static_cast<int64_t>(p - 1) * q || n_pairs >= (INT64_C(1) << 31)) return PRS_EINVAL;
-    if (dtype != PRS_I32 && dtype != PRS_F32) return PRS_EINVAL;
+    const int elem = dtype & 0xFF, op = dtype & ~0xFF;
+    if ((elem != PRS_I32 && elem != PRS_F32 && elem != PRS_F64 && elem != PRS_I64) || (op != PRS_OP_SUM && op != PRS_OP_MAX))
+        return PRS_EINVAL;
     if (n_elems < 0 || stride_elems < n_elems) return PRS_EINVAL;
     if (seg_elem_offset[0] != 0 || seg_elem_offset[q] != n_elems) return PRS_EINVAL;
     for (int k = 0; k < q; ++k)
         if (seg_elem_offset[k + 1] < seg_elem_offset[k]) return PRS_EINVAL;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
     if (workspace_bytes < replay_workspace_bytes(p, q)) return PRS_ENOSPC;
-    ReplayLaunch L{p, q, seg_elem_offset, src, dst, seg, n_pairs, in, stride_elems, n_elems, dtype, out, status,
+    ReplayLaunch L{p, q, seg_elem_offset, src, dst, seg, n_pairs, in, stride_elems, n_elems, elem, op, out, status,
                    static_cast<char *>(workspace), static_cast<hipStream_t>(stream)};
     return launch_replay(L) == hipSuccess ? PRS_OK : PRS_EDEVICE;
 }

@@ -89,7 +89,7 @@ struct ReplayLaunch {
     int64_t n_pairs;
     const void *in;
     int64_t stride_elems, n_elems;
-    int dtype;
+    int dtype, op;
     void *out;
     int32_t *status;
     char *workspace;

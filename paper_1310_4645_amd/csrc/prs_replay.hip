@@ -157,36 +157,75 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
     atomicMax(&flags[2], deepest + 1);
 }
 
-template <typename E> struct Vec4 { E v[4]; };
+// The combine operation of a replay.  Sum: wrapping for integers, one IEEE addition (no FMA) for floating point.
+// Max: the larger operand; floating point is compared in the IEEE total order (-NaN < -inf < ... < -0 < +0 < ... <
+// +inf < +NaN), which is a comparison of the bit patterns as sign-magnitude integers, so the result does not
+// depend on the order of the operands either.
+template <typename E> struct Bits;
+template <> struct Bits<float> { using I = int32_t; };
+template <> struct Bits<double> { using I = int64_t; };
 
-template <typename E> __device__ __forceinline__ E add1(E a, E b);
-template <> __device__ __forceinline__ float add1<float>(float a, float b) { return a + b; }
-template <> __device__ __forceinline__ int32_t add1<int32_t>(int32_t a, int32_t b)
+template <typename E> __device__ __forceinline__ E total_max(E a, E b)
 {
-    return static_cast<int32_t>(static_cast<uint32_t>(a) + static_cast<uint32_t>(b));
+    using I = typename Bits<E>::I;
+    constexpr I kMag = static_cast<I>(~(static_cast<I>(1) << (sizeof(I) * 8 - 1)));     // all bits but the sign
+    I ia, ib;
+    __builtin_memcpy(&ia, &a, sizeof(E));
+    __builtin_memcpy(&ib, &b, sizeof(E));
+    const I ka = ia < 0 ? static_cast<I>(ia ^ kMag) : ia, kb = ib < 0 ? static_cast<I>(ib ^ kMag) : ib;
+    return ka < kb ? b : a;
 }
+
+template <typename E, int OP> struct Combine;
+template <> struct Combine<int32_t, PRS_OP_SUM> {
+    static __device__ __forceinline__ int32_t identity() { return 0; }
+    static __device__ __forceinline__ int32_t apply(int32_t a, int32_t b) { return static_cast<int32_t>(static_cast<uint32_t>(a) + static_cast<uint32_t>(b)); }
+};
+template <> struct Combine<int64_t, PRS_OP_SUM> {
+    static __device__ __forceinline__ int64_t identity() { return 0; }
+    static __device__ __forceinline__ int64_t apply(int64_t a, int64_t b) { return static_cast<int64_t>(static_cast<uint64_t>(a) + static_cast<uint64_t>(b)); }
+};
+template <> struct Combine<float, PRS_OP_SUM> {
+    static __device__ __forceinline__ float identity() { return 0.0f; }
+    static __device__ __forceinline__ float apply(float a, float b) { return a + b; }
+};
+template <> struct Combine<double, PRS_OP_SUM> {
+    static __device__ __forceinline__ double identity() { return 0.0; }
+    static __device__ __forceinline__ double apply(double a, double b) { return a + b; }
+};
+template <> struct Combine<int32_t, PRS_OP_MAX> {
+    static __device__ __forceinline__ int32_t identity() { return INT32_MIN; }
+    static __device__ __forceinline__ int32_t apply(int32_t a, int32_t b) { return a < b ? b : a; }
+};
+template <> struct Combine<int64_t, PRS_OP_MAX> {
+    static __device__ __forceinline__ int64_t identity() { return INT64_MIN; }
+    static __device__ __forceinline__ int64_t apply(int64_t a, int64_t b) { return a < b ? b : a; }
+};
+template <> struct Combine<float, PRS_OP_MAX> {
+    static __device__ __forceinline__ float identity() { return __builtin_bit_cast(float, 0xFFFFFFFFu); }        // least in the total order
+    static __device__ __forceinline__ float apply(float a, float b) { return total_max<float>(a, b); }
+};
+template <> struct Combine<double, PRS_OP_MAX> {
+    static __device__ __forceinline__ double identity() { return __builtin_bit_cast(double, ~UINT64_C(0)); }
+    static __device__ __forceinline__ double apply(double a, double b) { return total_max<double>(a, b); }
+};
 
 template <typename E, int VEC> struct Acc {
     E v[VEC];
-    __device__ __forceinline__ void add(const Acc &o)
-    {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[i] = add1<E>(v[i], o.v[i]);
-    }
 };
 
 template <typename E, int VEC>
 __device__ __forceinline__ Acc<E, VEC> load_elems(const E *ptr, int nvalid)
 {
     Acc<E, VEC> a;
-    if (VEC == 4 && nvalid == 4) {
+    if (VEC * sizeof(E) == 16 && nvalid == VEC) {
         const float4 f = *reinterpret_cast<const float4 *>(ptr);
         const E *fe = reinterpret_cast<const E *>(&f);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) a.v[i] = fe[i];
     } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) a.v[i] = i < nvalid ? ptr[i] : E(0);
+        for (int i = 0; i < VEC; ++i) a.v[i] = i < nvalid ? ptr[i] : E(0);    // elements past the end are never stored
     }
     return a;
 }
@@ -194,7 +233,7 @@ __device__ __forceinline__ Acc<E, VEC> load_elems(const E *ptr, int nvalid)
 template <typename E, int VEC>
 __device__ __forceinline__ void store_elems(E *ptr, const Acc<E, VEC> &a, int nvalid)
 {
-    if (VEC == 4 && nvalid == 4) {
+    if (VEC * sizeof(E) == 16 && nvalid == VEC) {
         float4 f;
         E *fe = reinterpret_cast<E *>(&f);
 #pragma unroll
@@ -211,7 +250,7 @@ __device__ __forceinline__ void store_elems(E *ptr, const Acc<E, VEC> &a, int nv
 // groups of kPrefetch rows are in flight while the group before them is added up.  The LDS allocation fixes
 // the depth D (8, 16 or 24 levels, the fewer the more blocks fit on a CU); every variant is launched and only
 // the one that fits the schedule's trees (flags[2], found by replay_build) runs.
-template <typename E, int VEC>
+template <typename E, int VEC, int OP>
 __device__ __forceinline__ void replay_step(Acc<E, VEC> &acc, int &sp, E *stk, uint32_t ent, const Acc<E, VEC> &val)
 {
     if ((ent >> 20) & 1u) {
@@ -222,17 +261,18 @@ __device__ __forceinline__ void replay_step(Acc<E, VEC> &acc, int &sp, E *stk, u
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc.v[i] = val.v[i];
     } else {
-        acc.add(val);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc.v[i] = Combine<E, OP>::apply(acc.v[i], val.v[i]);
     }
     for (int np = static_cast<int>(ent >> 21); np > 0; --np) {
         --sp;
         const E *slot = stk + static_cast<size_t>(sp) * kReplayThreads * VEC;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc.v[i] = add1<E>(slot[i], acc.v[i]);   // saved partial sum + finished subtree
+        for (int i = 0; i < VEC; ++i) acc.v[i] = Combine<E, OP>::apply(slot[i], acc.v[i]);   // saved partial result, then the finished subtree
     }
 }
 
-template <typename E, int VEC, int D>
+template <typename E, int VEC, int D, int OP>
 __global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const int64_t *__restrict__ offsets,
                                                                 const uint32_t *__restrict__ prog, const E *__restrict__ in,
                                                                 int64_t stride, E *__restrict__ out,
@@ -250,7 +290,7 @@ __global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const
     const uint32_t *pg = prog + static_cast<size_t>(k) * p;
     Acc<E, VEC> acc;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc.v[i] = E(0);
+    for (int i = 0; i < VEC; ++i) acc.v[i] = Combine<E, OP>::identity();
     E *const stk = reinterpret_cast<E *>(lds_raw) + static_cast<size_t>(threadIdx.x) * VEC;   // this thread's column of the LDS stack
     int sp = 0;
     const bool full = b0 + static_cast<int64_t>(kReplayThreads) * VEC <= hi;   // every thread of the block has VEC elements
@@ -271,14 +311,14 @@ __global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const
             for (int u = 0; u < kPrefetch; ++u) valB[u] = load_elems<E, VEC>(in + static_cast<int64_t>(entB[u] & 0xFFFFFu) * stride + e0, VEC);
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u)
-                if (base + u < p) replay_step<E, VEC>(acc, sp, stk, entA[u], valA[u]);
+                if (base + u < p) replay_step<E, VEC, OP>(acc, sp, stk, entA[u], valA[u]);
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u) entA[u] = row(base + 2 * kPrefetch + u);
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u) valA[u] = load_elems<E, VEC>(in + static_cast<int64_t>(entA[u] & 0xFFFFFu) * stride + e0, VEC);
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u)
-                if (base + kPrefetch + u < p) replay_step<E, VEC>(acc, sp, stk, entB[u], valB[u]);
+                if (base + kPrefetch + u < p) replay_step<E, VEC, OP>(acc, sp, stk, entB[u], valB[u]);
         }
         store_elems<E, VEC>(out + e0, acc, VEC);
     } else if (e0 < hi) {
@@ -286,7 +326,7 @@ __global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const
         const int nvalid = hi - e0 >= VEC ? VEC : static_cast<int>(hi - e0);
         for (int idx = 0; idx < p; ++idx) {
             const uint32_t ent = pg[idx];
-            replay_step<E, VEC>(acc, sp, stk, ent, load_elems<E, VEC>(in + static_cast<int64_t>(ent & 0xFFFFFu) * stride + e0, nvalid));
+            replay_step<E, VEC, OP>(acc, sp, stk, ent, load_elems<E, VEC>(in + static_cast<int64_t>(ent & 0xFFFFFu) * stride + e0, nvalid));
         }
         store_elems<E, VEC>(out + e0, acc, nvalid);
     }
@@ -297,31 +337,32 @@ __global__ void replay_write_status(const int32_t *flags, int32_t *status)
     if (threadIdx.x == 0 && status) *status = flags[0] ? 1 : (flags[1] ? 2 : 0);
 }
 
-static size_t replay_lds_bytes(int vec, int depth) { return static_cast<size_t>(depth) * kReplayThreads * vec * 4; }
+static size_t replay_lds_bytes(int vec, int depth, size_t elem) { return static_cast<size_t>(depth) * kReplayThreads * vec * elem; }
+
+template <typename E, int VEC, int OP>
+static void launch_replay_depths(const ReplayLaunch &L, const ReplayWs &w, int64_t max_len)
+{
+    const E *in = static_cast<const E *>(L.in);
+    E *out = static_cast<E *>(L.out);
+    const int64_t groups = (max_len + VEC - 1) / VEC;
+    dim3 grid(static_cast<unsigned>((groups + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
+    hipLaunchKernelGGL((replay_kernel<E, VEC, 8, OP>), grid, dim3(kReplayThreads), replay_lds_bytes(VEC, 8, sizeof(E)), L.stream, L.p,
+                       w.offsets, w.prog, in, L.stride_elems, out, w.flags);
+    hipLaunchKernelGGL((replay_kernel<E, VEC, 16, OP>), grid, dim3(kReplayThreads), replay_lds_bytes(VEC, 16, sizeof(E)), L.stream, L.p,
+                       w.offsets, w.prog, in, L.stride_elems, out, w.flags);
+    hipLaunchKernelGGL((replay_kernel<E, VEC, 24, OP>), grid, dim3(kReplayThreads), replay_lds_bytes(VEC, 24, sizeof(E)), L.stream, L.p,
+                       w.offsets, w.prog, in, L.stride_elems, out, w.flags);
+}
 
 template <typename E>
 static hipError_t launch_replay_t(const ReplayLaunch &L, const ReplayWs &w, int64_t max_len, bool vec_ok)
 {
-    const E *in = static_cast<const E *>(L.in);
-    E *out = static_cast<E *>(L.out);
+    constexpr int kVec = 16 / sizeof(E);                           // 16 bytes per lane and row
     if (max_len > 0) {
-        if (vec_ok) {
-            const int64_t groups = (max_len + 3) / 4;
-            dim3 grid(static_cast<unsigned>((groups + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
-            hipLaunchKernelGGL((replay_kernel<E, 4, 8>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 8), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
-            hipLaunchKernelGGL((replay_kernel<E, 4, 16>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 16), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
-            hipLaunchKernelGGL((replay_kernel<E, 4, 24>), grid, dim3(kReplayThreads), replay_lds_bytes(4, 24), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
+        if (L.op == PRS_OP_MAX) {
+            if (vec_ok) launch_replay_depths<E, kVec, PRS_OP_MAX>(L, w, max_len); else launch_replay_depths<E, 1, PRS_OP_MAX>(L, w, max_len);
         } else {
-            dim3 grid(static_cast<unsigned>((max_len + kReplayThreads - 1) / kReplayThreads), static_cast<unsigned>(L.q));
-            hipLaunchKernelGGL((replay_kernel<E, 1, 8>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 8), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
-            hipLaunchKernelGGL((replay_kernel<E, 1, 16>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 16), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
-            hipLaunchKernelGGL((replay_kernel<E, 1, 24>), grid, dim3(kReplayThreads), replay_lds_bytes(1, 24), L.stream, L.p, w.offsets, w.prog, in,
-                               L.stride_elems, out, w.flags);
+            if (vec_ok) launch_replay_depths<E, kVec, PRS_OP_SUM>(L, w, max_len); else launch_replay_depths<E, 1, PRS_OP_SUM>(L, w, max_len);
         }
     }
     return hipGetLastError();
@@ -332,12 +373,13 @@ hipError_t launch_replay(const ReplayLaunch &L)
 {
     const ReplayWs w = carve_replay(L.workspace, L.p, L.q);
     int64_t max_len = 0;
-    bool vec_ok = (L.stride_elems % 4 == 0) && (reinterpret_cast<uintptr_t>(L.in) % 16 == 0) &&
+    const int vec = (L.dtype == PRS_F64 || L.dtype == PRS_I64) ? 2 : 4;       // elements in 16 bytes
+    bool vec_ok = (L.stride_elems % vec == 0) && (reinterpret_cast<uintptr_t>(L.in) % 16 == 0) &&
                   (reinterpret_cast<uintptr_t>(L.out) % 16 == 0);
     for (int k = 0; k < L.q; ++k) {
         const int64_t len = L.seg_elem_offset[k + 1] - L.seg_elem_offset[k];
         if (len > max_len) max_len = len;
-        if (L.seg_elem_offset[k] % 4 != 0) vec_ok = false;
+        if (L.seg_elem_offset[k] % vec != 0) vec_ok = false;
     }
     hipError_t err = hipSuccess;
     for (int base = 0; base < L.q + 1; base += kOffsetChunk) {
@@ -355,7 +397,12 @@ hipError_t launch_replay(const ReplayLaunch &L)
         hipLaunchKernelGGL(replay_build<false>, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), 0, L.stream, L.p, L.q,
                            L.src, L.dst, L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
     if ((err = hipGetLastError()) != hipSuccess) return err;
-    err = L.dtype == PRS_F32 ? launch_replay_t<float>(L, w, max_len, vec_ok) : launch_replay_t<int32_t>(L, w, max_len, vec_ok);
+    switch (L.dtype) {
+    case PRS_F32: err = launch_replay_t<float>(L, w, max_len, vec_ok); break;
+    case PRS_F64: err = launch_replay_t<double>(L, w, max_len, vec_ok); break;
+    case PRS_I64: err = launch_replay_t<int64_t>(L, w, max_len, vec_ok); break;
+    default: err = launch_replay_t<int32_t>(L, w, max_len, vec_ok); break;
+    }
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(replay_write_status, dim3(1), dim3(64), 0, L.stream, w.flags, L.status);
     return hipGetLastError();

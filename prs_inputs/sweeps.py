@@ -125,24 +125,29 @@ def replay_config() -> SweepConfigs:
 
 def replay_buffers(p: int, n_elems: int, dtype: str, seed: int = SEED_REPLAY,
                    elem_index: np.ndarray | None = None) -> np.ndarray:
-    """p buffers of n_elems values: int32 uniform in [-2^20, 2^20] or fp32
-    standard normal (Box-Muller on two counter-based uniforms).  Each value is
+    """p buffers of n_elems values: int32 uniform in [-2^20, 2^20], int64 uniform in
+    [-2^40, 2^40], or fp32 / fp64 standard normal (Box-Muller on two counter-based
+    uniforms).  Each value is
     a function of (seed, buffer, element), so `elem_index` may select any
     subset of element columns of the full-size problem."""
     if elem_index is None:
         elem_index = np.arange(n_elems, dtype=np.uint64)
     e = np.asarray(elem_index, dtype=np.uint64)
-    out = np.empty((p, e.shape[0]), dtype=np.int32 if dtype == "i32" else np.float32)
+    kinds = {"i32": np.int32, "f32": np.float32, "i64": np.int64, "f64": np.float64}
+    if dtype not in kinds:
+        raise ValueError("dtype must be one of " + ", ".join(kinds))
+    out = np.empty((p, e.shape[0]), dtype=kinds[dtype])
     for i in range(p):
         key = e + np.uint64(i) * np.uint64(n_elems)
         if dtype == "i32":
             u = _uniform01(seed, key, 0)
             out[i] = (np.floor(u * (2 ** 21 + 1)) - 2 ** 20).astype(np.int32)
-        elif dtype == "f32":
+        elif dtype == "i64":
+            u = _uniform01(seed, key, 3)
+            out[i] = (np.floor(u * (2 ** 41 + 1)) - 2 ** 40).astype(np.int64)
+        else:
             u1 = _uniform01(seed, key, 1)
             u2 = _uniform01(seed, key, 2)
             r = np.sqrt(-2.0 * np.log1p(-u1))
-            out[i] = (r * np.cos(2.0 * np.pi * u2)).astype(np.float32)
-        else:
-            raise ValueError("dtype must be 'i32' or 'f32'")
+            out[i] = (r * np.cos(2.0 * np.pi * u2)).astype(kinds[dtype])
     return out

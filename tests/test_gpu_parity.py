@@ -456,6 +456,59 @@ def test_replay_small_ragged(prs, model, dtype):
     _replay_case(prs, 130, [4] * q, model, np.arange(q + 1, dtype=np.int64) * 2048, dtype, strided=True)
 
 
+def _replay_pairs(prs, p, q, pairs, seg_off, dtype, op="sum", strided=False, special=False):
+    """One replay of a given pair list: the library against the oracle, bit for bit."""
+    import torch
+    src, dst, seg = pairs
+    n = int(seg_off[-1])
+    buf = prs_inputs.replay_buffers(p, n, dtype)
+    if special:                                                         # signed zeros and a NaN in floating-point columns
+        buf[:, 0] = -0.0; buf[p // 2, 0] = 0.0
+        buf[:, 1] = -0.0
+        buf[p - 1, 2] = np.nan
+    want = O.replay(p, seg_off, src, dst, seg, buf, op)
+    dbuf = torch.from_numpy(buf).cuda()
+    if strided:
+        wide = torch.zeros((p, n + 6), dtype=dbuf.dtype, device="cuda")
+        wide[:, :n] = dbuf
+        dbuf = wide[:, :n]
+    out, st = prs.replay_reduction(p, q, seg_off, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda(),
+                                   torch.from_numpy(seg).cuda(), dbuf, op=prs.PRS_OP_MAX if op == "max" else prs.PRS_OP_SUM)
+    _sync()
+    assert int(st.item()) == 0
+    assert _np(out).tobytes() == want.tobytes(), (p, q, dtype, op)
+
+
+@pytest.mark.parametrize("op", ["sum", "max"])
+@pytest.mark.parametrize("dtype", ["i32", "f32", "i64", "f64"])
+def test_replay_element_types_and_operations(prs, dtype, op):
+    """Uni- and bi-greedy schedules on 32- and 64-bit integers and floating point, summed or maximised:
+    vector path (aligned segments), scalar path (unaligned), ragged ends, strided rows."""
+    q = 5
+    sizes = [4] * 4 + [2]
+    for model in (0, 1):
+        s = (O.uni_greedy if model == 0 else O.bi_greedy)(29, sizes, 2, 1, 1)
+        pairs = (s.src, s.dst, s.seg)
+        _replay_pairs(prs, 29, q, pairs, np.array([0, 1000, 2000, 3000, 4000, 4321], np.int64), dtype, op)
+        _replay_pairs(prs, 29, q, pairs, np.array([0, 37, 74, 111, 148, 151], np.int64), dtype, op)
+        _replay_pairs(prs, 29, q, pairs, np.arange(q + 1, dtype=np.int64) * 1536, dtype, op, strided=True)
+    if dtype in ("f32", "f64") and op == "max":
+        s = O.uni_greedy(29, sizes, 2, 1, 1)
+        _replay_pairs(prs, 29, q, (s.src, s.dst, s.seg), np.arange(q + 1, dtype=np.int64) * 512, dtype, op, special=True)
+
+
+@pytest.mark.parametrize("tree", ["pipeline", "binomial", "binary"])
+def test_replay_of_baseline_trees(prs, tree):
+    """The same kernel on the trees of Section 4 (pipeline chain: the deepest combine tree there is;
+    binomial; binary), every segment through the same tree."""
+    import baseline_trees as B
+    build = getattr(B, tree)
+    for p, q, per in ((2, 1, 5), (13, 3, 1000), (64, 4, 2048), (200, 2, 700)):
+        off = np.arange(q + 1, dtype=np.int64) * per
+        for dtype in ("f32", "i32", "f64"):
+            _replay_pairs(prs, p, q, build(p, q), off, dtype)
+
+
 def test_replay_rejects_a_schedule_that_is_not_a_tree(prs):
     import torch
     p, q = 4, 1

@@ -433,6 +433,52 @@ def test_replay_follows_the_schedule_order():
     assert star[0] == np.float32(1.0)
 
 
+def test_replay_other_element_types_and_maximum():
+    """Replay with 64-bit elements and with the maximum as the combine: integers wrap and give the plain
+    sum modulo 2^64; the fp64 association is the schedule's; the maximum of a column does not depend on the
+    schedule, orders -0 below +0 and puts a NaN with a clear sign bit on top."""
+    p, q = 11, 3
+    off = np.array([0, 7, 14, 18], np.int64)
+    s = O.uni_greedy(p, [7, 7, 4], 2, 1, 1)
+    big = prs_inputs.replay_buffers(p, 18, "i64") + (np.int64(1) << 61)           # 11 x 2^61 passes 2^63
+    want = np.zeros(18, np.uint64)
+    for row in big:
+        want = want + row.view(np.uint64)
+    assert np.array_equal(O.replay(p, off, s.src, s.dst, s.seg, big).view(np.uint64), want)
+    buf = np.array([[1.0], [2.0 ** -53], [2.0 ** -53]], dtype=np.float64)
+    one = np.array([0, 1], np.int64)
+    assert O.replay(3, one, [2, 1], [1, 0], [0, 0], buf)[0] == 1.0 + 2.0 ** -52    # b0 + (b1 + b2)
+    assert O.replay(3, one, [1, 2], [0, 0], [0, 0], buf)[0] == 1.0                 # (b0 + b1) + b2
+    for kind in ("i32", "i64", "f32", "f64"):
+        b = prs_inputs.replay_buffers(p, 18, kind)
+        assert np.array_equal(O.replay(p, off, s.src, s.dst, s.seg, b, "max"), b.max(axis=0))
+    z = np.array([[-0.0, -1.0, -0.0], [0.0, np.nan, -0.0], [-0.0, 5.0, -0.0]], np.float32)
+    r = O.replay(3, np.array([0, 3], np.int64), [2, 1], [1, 0], [0, 0], z, "max")
+    assert not np.signbit(r[0]) and r[0] == 0 and np.isnan(r[1]) and np.signbit(r[2])
+    assert np.array_equal(O.total_order_key(np.array([-np.inf, -1.0, -0.0, 0.0, 1.0, np.inf])).argsort(), np.arange(6))
+
+
+def test_replay_of_baseline_trees_has_their_association():
+    """Section 4's trees as schedules: the pipeline folds from the far end, b0 + (b1 + (b2 + ...)); the
+    binomial tree adds neighbours, then neighbours of neighbours; integers give the plain sum for all."""
+    import baseline_trees as B
+    p, q = 8, 2
+    off = np.array([0, 5, 9], np.int64)
+    bf = prs_inputs.replay_buffers(p, 9, "f32")
+    chain = bf[p - 1].copy()
+    for i in range(p - 2, -1, -1):
+        chain = bf[i] + chain
+    assert np.array_equal(O.replay(p, off, *B.pipeline(p, q), bf), chain)
+    pairwise = ((bf[0] + bf[1]) + (bf[2] + bf[3])) + ((bf[4] + bf[5]) + (bf[6] + bf[7]))
+    assert np.array_equal(O.replay(p, off, *B.binomial(p, q), bf), pairwise)
+    heap = (bf[0] + ((bf[2] + bf[6]) + bf[5])) + ((bf[1] + bf[4]) + (bf[3] + bf[7]))
+    assert np.array_equal(O.replay(p, off, *B.binary(p, q), bf), heap)
+    for tree in (B.pipeline, B.binomial, B.binary):
+        for pp in (2, 3, 13):
+            bi = prs_inputs.replay_buffers(pp, 9, "i32")
+            assert np.array_equal(O.replay(pp, off, *tree(pp, q), bi), bi.sum(axis=0, dtype=np.int64).astype(np.int32))
+
+
 # --------------------------------------------------------------------------- best segmentation (Sections 5.2, 6.1)
 def _table1_pipeline_uni(p, q, m, a, b, g):
     sz = -(-m // q)
