@@ -324,6 +324,47 @@ def test_optimal_segmentation_matches_trying_each_count(prs, model, cost):
     assert st[2] == 1 and np.all(st[ok] == 0) and _np(got["q_greedy"])[2] == -1
 
 
+def test_theoretical_experiment_grid_of_section_5_2(prs):
+    """The parameter grid of the paper's theoretical experiments (alpha in {0,1,10,100,1000}, beta = 1,
+    gamma in {0,1}, p = 4..1024, m = 4..65536 bytes, powers of two), every algorithm at its best
+    power-of-two segment count, on the GPU: no standard algorithm ever beats uni-greedy (Theorem 1), small
+    messages are reduced best unsegmented, where greedy is the binomial tree, and at p = 64, alpha = 10,
+    gamma = 0 the largest gain over the best standard algorithm is about 50 % (Figure 4).  A sample of
+    the grid is compared with the oracle trying each count."""
+    probs = [(p, m, a, g) for a in (0, 1, 10, 100, 1000) for g in (0, 1) for p in (2 ** k for k in range(2, 11))
+             for m in (2 ** k for k in range(2, 17))]
+    n = len(probs)
+    host = prs_inputs.SweepConfigs(np.array([x[0] for x in probs], np.int32), np.zeros(n, np.int32),
+                                   np.array([x[1] for x in probs], np.int64), np.array([x[2] for x in probs], np.int64),
+                                   np.ones(n, np.int64), np.array([x[3] for x in probs], np.int64), "i64")
+    dev = prs.DeviceConfigs.from_host(host)
+    best = prs.optimal_segmentation_batch(dev, prs.PRS_UNI, 1024, 65536)
+    one = prs.DeviceConfigs.from_host(prs_inputs.SweepConfigs(host.p, np.ones(n, np.int32), host.m, host.alpha, host.beta,
+                                                               host.gamma, "i64"))
+    unsegmented = prs.simulate_completion_batch(one, prs.PRS_UNI, 1024, 1)
+    _sync()
+    assert np.all(_np(best["cfg_status"]) == 0)
+    tg, tp, ty = (_np(best[k]).astype(np.float64) for k in ("T_greedy", "T_pipeline", "T_binary"))
+    tb = _np(unsegmented["binomial"]).astype(np.float64)
+    assert np.array_equal(_np(unsegmented["greedy"]), _np(unsegmented["binomial"]))      # q = 1: greedy is the binomial tree
+    ratio = np.minimum(np.minimum(tb, tp), ty) / tg
+    assert np.all(ratio >= 1.0)
+    fig4 = [i for i, x in enumerate(probs) if x[0] == 64 and x[2] == 10 and x[3] == 0]
+    r4 = {probs[i][1]: ratio[i] for i in fig4}
+    assert r4[4] == 1.0 and r4[16] == 1.0 and _np(best["q_greedy"])[fig4[0]] == 1
+    assert 1.4 <= max(r4.values()) <= 1.65 and max(r4, key=r4.get) in (256, 512, 1024)
+    assert r4[65536] < r4[16384] < r4[4096] and r4[65536] < 1.1                         # the pipeline catches up
+    # the region of the largest gain widens with p (Figure 5): count the message sizes with a gain above 30 %
+    wide = {p: sum(1 for i, x in enumerate(probs) if x[0] == p and x[2] == 10 and x[3] == 0 and ratio[i] > 1.3)
+            for p in (16, 64, 256, 1024)}
+    assert wide[16] <= wide[64] <= wide[256] <= wide[1024] and wide[1024] > wide[16]
+    idx = np.array([i for i, x in enumerate(probs) if x[0] <= 32 and x[1] <= 256][::3])
+    ref = O.optimal_segmentation(host.take(idx), O.UNI, 65536)
+    for key in ("greedy", "pipeline", "binary", "revopt"):
+        assert np.array_equal(_np(best["T_" + key])[idx], ref["T_" + key]), key
+        assert np.array_equal(_np(best["q_" + key])[idx], ref["q_" + key]), key
+
+
 # --------------------------------------------------------------------------- unequal segmentation (Section 8)
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 
