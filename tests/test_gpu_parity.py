@@ -365,6 +365,42 @@ def test_theoretical_experiment_grid_of_section_5_2(prs):
         assert np.array_equal(_np(best["q_" + key])[idx], ref["q_" + key]), key
 
 
+def test_theoretical_experiment_bidirectional_section_6_1(prs):
+    """Section 6.1 with the machine of Figure 6 (alpha = 50000, beta = 6, gamma = 1), p = 4..1024, m = 2^10..2^27,
+    every algorithm at its best power-of-two segment count up to 512: bi-greedy needs exactly the rounds of the
+    reversed optimal broadcast (Table III), no tree algorithm beats it, it equals the binomial tree for small
+    messages, the pipeline approaches it for large ones, and the butterfly comes close only for mid-size
+    messages.  A sample is compared with the oracle trying each count."""
+    probs = [(p, m) for p in (2 ** k for k in range(2, 11)) for m in (2 ** k for k in range(10, 28))]
+    n = len(probs)
+    host = prs_inputs.SweepConfigs(np.array([x[0] for x in probs], np.int32), np.zeros(n, np.int32),
+                                   np.array([x[1] for x in probs], np.int64), np.full(n, 50000, np.int64),
+                                   np.full(n, 6, np.int64), np.ones(n, np.int64), "i64")
+    dev = prs.DeviceConfigs.from_host(host)
+    best = prs.optimal_segmentation_batch(dev, prs.PRS_BI, 1024, 512)
+    one = prs.DeviceConfigs.from_host(prs_inputs.SweepConfigs(host.p, np.ones(n, np.int32), host.m, host.alpha, host.beta,
+                                                               host.gamma, "i64"))
+    uns = prs.simulate_completion_batch(one, prs.PRS_BI, 1024, 1)
+    _sync()
+    assert np.all(_np(best["cfg_status"]) == 0)
+    assert np.array_equal(_np(best["T_greedy"]), _np(best["T_revopt"])) and np.array_equal(_np(best["q_greedy"]), _np(best["q_revopt"]))
+    tg = _np(best["T_greedy"]).astype(np.float64)
+    rb, rp, ry = (_np(t).astype(np.float64) / tg for t in (uns["binomial"], best["T_pipeline"], best["T_binary"]))
+    rf = _np(uns["butterfly"]) / tg
+    assert np.all(np.minimum(np.minimum(rb, rp), ry) >= 1.0)
+    row = [i for i, x in enumerate(probs) if x[0] == 64]
+    assert rb[row[0]] == 1.0 and rb[row[1]] == 1.0 and np.all(np.diff(rb[row]) >= 0) and rb[row[-1]] > 5
+    assert np.all(np.diff(rp[row]) < 0) and rp[row[-1]] < 1.2 and rp[row[0]] > 5
+    assert np.all(ry[row] == 2.0)                                        # twice the rounds, whatever the segment size
+    lowest = int(np.argmin(rf[row]))
+    assert 0 < lowest < len(row) - 1 and 1.0 < rf[row][lowest] < 1.1 and rf[row[0]] > 1.5 and rf[row[-1]] > 1.5
+    idx = np.array([i for i, x in enumerate(probs) if x[0] <= 16 and x[1] <= 2 ** 15][::2])
+    ref = O.optimal_segmentation(host.take(idx), O.BI, 512)
+    for key in ("greedy", "pipeline", "binary", "revopt"):
+        assert np.array_equal(_np(best["T_" + key])[idx], ref["T_" + key]), key
+        assert np.array_equal(_np(best["q_" + key])[idx], ref["q_" + key]), key
+
+
 # --------------------------------------------------------------------------- unequal segmentation (Section 8)
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 
