@@ -29,11 +29,24 @@ __global__ void plan_clear(PlanHeader *h)
     for (int k = i; k < kClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
 }
 
+constexpr int kPlanThreads = 256;
+constexpr int kPlanBins = kClasses * kWorkBuckets;
+
+// Both passes count inside the block first (LDS) and touch the global counters once per block and bin: with one
+// global atomic per configuration, a batch of millions spends its time queueing on a few dozen addresses.
 template <typename T>
-__global__ void plan_hist(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim, PlanHeader *h)
+__global__ __launch_bounds__(kPlanThreads) void plan_hist(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim,
+                                                          PlanHeader *h)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < n) atomicAdd(&h->hist[plan_bucket<T>(cfg, i, p_max, q_max, lim)], 1);
+    __shared__ int32_t local[kPlanBins];
+    const int tid = static_cast<int>(threadIdx.x);
+    for (int k = tid; k < kPlanBins; k += kPlanThreads) local[k] = 0;
+    __syncthreads();
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kPlanThreads + tid;
+    if (i < n) atomicAdd(&local[plan_bucket<T>(cfg, i, p_max, q_max, lim)], 1);
+    __syncthreads();
+    for (int k = tid; k < kPlanBins; k += kPlanThreads)
+        if (local[k] != 0) atomicAdd(&h->hist[k], local[k]);
 }
 
 __global__ void plan_scan(PlanHeader *h)
@@ -51,28 +64,38 @@ __global__ void plan_scan(PlanHeader *h)
 }
 
 template <typename T>
-__global__ void plan_scatter(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim, PlanHeader *h,
-                             int32_t *order)
+__global__ __launch_bounds__(kPlanThreads) void plan_scatter(ConfigArrays cfg, int64_t n, int32_t p_max, int32_t q_max, ClassLimits lim,
+                                                             PlanHeader *h, int32_t *order)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int b = plan_bucket<T>(cfg, i, p_max, q_max, lim);
-    const int32_t pos = h->start[b] + atomicAdd(&h->cursor[b], 1);
-    order[pos] = static_cast<int32_t>(i);
+    __shared__ int32_t local[kPlanBins];                             // configurations of this block per bin, then the bin's first slot
+    const int tid = static_cast<int>(threadIdx.x);
+    for (int k = tid; k < kPlanBins; k += kPlanThreads) local[k] = 0;
+    __syncthreads();
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kPlanThreads + tid;
+    int b = 0, rank = 0;
+    if (i < n) {
+        b = plan_bucket<T>(cfg, i, p_max, q_max, lim);
+        rank = atomicAdd(&local[b], 1);
+    }
+    __syncthreads();
+    for (int k = tid; k < kPlanBins; k += kPlanThreads)
+        if (local[k] != 0) local[k] = h->start[k] + atomicAdd(&h->cursor[k], local[k]);
+    __syncthreads();
+    if (i < n) order[local[b] + rank] = static_cast<int32_t>(i);
 }
 
 hipError_t launch_plan(const PlanLaunch &L)
 {
-    const unsigned blocks = static_cast<unsigned>((L.n + 255) / 256);
+    const unsigned blocks = static_cast<unsigned>((L.n + kPlanThreads - 1) / kPlanThreads);
     hipLaunchKernelGGL(plan_clear, dim3(1), dim3(256), 0, L.stream, L.header);
     if (L.cost == PRS_COST_I64) {
-        hipLaunchKernelGGL((plan_hist<int64_t>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
+        hipLaunchKernelGGL((plan_hist<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
         hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
-        hipLaunchKernelGGL((plan_scatter<int64_t>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
+        hipLaunchKernelGGL((plan_scatter<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     } else {
-        hipLaunchKernelGGL((plan_hist<double>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
+        hipLaunchKernelGGL((plan_hist<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
         hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
-        hipLaunchKernelGGL((plan_scatter<double>), dim3(blocks), dim3(256), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
+        hipLaunchKernelGGL((plan_scatter<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     }
     return hipGetLastError();
 }
