@@ -130,7 +130,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         for (int k = 0; k < kClasses; ++k) {
             ClassSpec &c = L.cls[k];
             c.kind = sched ? kUniSched : kUniTimes; c.lpc = 0; c.rows_per_group = 0; c.lds = true; c.lds_bitmap_bytes = 0;
-            c.p_cap = (p_max + 3) / 4 * 4;                       // keeps every per-lane array 8-byte aligned
+            c.p_cap = (p_max + 15) / 16 * 16;                    // keeps every per-lane array 64-byte aligned
             c.lds_bytes = sched ? uni_sched_lds_bytes() : uni_times_lds_bytes();
             c.slot_bytes = k != 0 ? 0 : (sched ? uni_sched_slot_bytes(c.p_cap) : uni_times_slot_bytes(c.p_cap));
             int64_t g = static_cast<int64_t>(kLdsPerCU / c.lds_bytes) * kCUs;

@@ -78,10 +78,10 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     T lastS = 0;                    // running value of my stream (0 before the first pair of a segment)
     T lastBx = 0; int brun = 0;     // value of the last B entry pushed, first pair of that value (relative)
     int32_t lastWi = 0, lastBi = 0; // sender of the last stream entry written, receiver of the last B entry
-    // Stream entries, receiver indices and pairs leave LDS in rows of four (16-byte stores).  Rows are written
+    // Stream entries and receiver indices leave LDS in rows of eight, pairs in rows of four.  Rows are written
     // every fourth iteration of the wavefront, by all lanes at once: done per lane whenever its row fills, the
     // row code would run in almost every iteration for a few lanes each.
-    int fW = 0, fB = 0, fO = 0;     // entries / receivers / pairs of my segment that have reached the workspace (multiples of 4)
+    int fW = 0, fB = 0, fO = 0;     // entries / receivers / pairs of my segment that have reached the workspace (multiples of 8, 8 and 4)
     int iter = 0;
     T cc = 0, gg = 0;
     bool farA = false, farB = false, anyFar = false;
@@ -286,26 +286,28 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             T *const myX = bufX(lane, par);
             int32_t *const myI = bufI(lane, par);
             const int w = wtot - segBase;
+            // stream entries and receivers in rows of eight (64 bytes of values: whole sectors of a cache line, which
+            // the L2 can no longer merge once millions of half-written lines are open)
+            if (have && k < q && fW + 8 <= w) {
+                T rx8[8]; int32_t ri8[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int rr = ((segBase + fW + j) & M) * kWave + lane;
+                    rx8[j] = ringX[rr]; ri8[j] = ringI[rr];
+                }
+                __builtin_memcpy(myX + fW, rx8, 64);
+                __builtin_memcpy(myI + fW, ri8, 32);
+                fW += 8;
+            }
+            if (have && k < q && fB + 8 <= ns) {
+                int32_t rb8[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) rb8[j] = ringB[((segBase + fB + j) & M) * kWave + lane];
+                __builtin_memcpy(bufB + fB, rb8, 32);
+                fB += 8;
+            }
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                if (have && k < q && fW + 4 <= w) {
-                    T rx4[4]; int32_t ri4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int rr = ((segBase + fW + j) & M) * kWave + lane;
-                        rx4[j] = ringX[rr]; ri4[j] = ringI[rr];
-                    }
-                    __builtin_memcpy(myX + fW, rx4, 32);
-                    __builtin_memcpy(myI + fW, ri4, 16);
-                    fW += 4;
-                }
-                if (have && k < q && fB + 4 <= ns) {
-                    int32_t rb4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) rb4[j] = ringB[((segBase + fB + j) & M) * kWave + lane];
-                    __builtin_memcpy(bufB + fB, rb4, 16);
-                    fB += 4;
-                }
                 if (have && k < q && fO + 4 <= ns) {
                     const int row = lane * kStage + (fO & (kStage - 1));
                     const int64_t o4 = out_base + static_cast<int64_t>(k) * n1 + fO;
