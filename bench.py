@@ -64,7 +64,7 @@ def cpu_baseline(host, seconds_hint=20.0):
 SEARCH_PROBLEMS = 10000
 
 # per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
-PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 6.1e8, "schedule_uni": 4.97e10, "schedule_bi": 2.48e10,
+PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 5.9e8, "schedule_uni": 9.11e10, "schedule_bi": 2.58e10,
                           "replay_i32": 4.33e9, "replay_f32": 4.33e9}
 
 
