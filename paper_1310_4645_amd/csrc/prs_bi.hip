@@ -119,32 +119,50 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
         if (ev > max_events) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         // ---- port and computation state of every processor at time t, as bit sets
         T minOld = kInf;
-        int cs = 0, cr = 0;
-        for (int w = 0; w < W; ++w) {
-            const int i = w * kWave + lane;
-            const bool in = i < p;
-            const T s = in ? S[i] : 0, r = in ? R[i] : 0, c1 = in ? C1[i] : 0;
-            const int32_t nsnt = in ? nsent[i] : q;
-            const bool live = in && (i == 0 || nsnt < q);          // still a member of some segment
-            const bool sf = live && i != 0 && s <= t;              // the root never sends
-            const bool rf = live && r <= t;
-            const bool busy = in && c1 <= t && t < r;              // computing now
-            const bool pend = in && t < c1;                        // computation scheduled ahead
-            const bool cF = busy || (pend && t + c.c_full > c1);
-            const bool cL = busy || (pend && t + c.c_last > c1);
-            if (in && s > t && s < minOld) minOld = s;
-            if (in && r > t && r < minOld) minOld = r;
-            const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL);
-            if (lane == 0) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; }
-            cs += __popcll(bsf & ~bcL);
-            cr += __popcll(brf & ~bcL);
+        int cs = 0, cr = 0, cu = 0;                  // free send ports, free receive ports, processors with either
+        // (four words of processors per round: their loads are issued together, ahead of the ballots and stores)
+        for (int w4 = 0; w4 < W; w4 += 4) {
+            T s4[4], r4[4], c4[4];
+            int32_t n4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = (w4 + u) * kWave + lane;
+                const bool in = i < p;
+                s4[u] = in ? S[i] : 0; r4[u] = in ? R[i] : 0; c4[u] = in ? C1[i] : 0;
+                n4[u] = in ? nsent[i] : q;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int w = w4 + u;
+                const int i = w * kWave + lane;
+                const bool in = i < p;
+                const T s = s4[u], r = r4[u], c1 = c4[u];
+                const int32_t nsnt = n4[u];
+                const bool live = in && (i == 0 || nsnt < q);          // still a member of some segment
+                const bool sf = live && i != 0 && s <= t;              // the root never sends
+                const bool rf = live && r <= t;
+                const bool busy = in && c1 <= t && t < r;              // computing now
+                const bool pend = in && t < c1;                        // computation scheduled ahead
+                const bool cF = busy || (pend && t + c.c_full > c1);
+                const bool cL = busy || (pend && t + c.c_last > c1);
+                if (in && s > t && s < minOld) minOld = s;
+                if (in && r > t && r < minOld) minOld = r;
+                const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL);
+                if (lane == 0 && w < W) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; }
+                cs += __popcll(bsf & ~bcL);
+                cr += __popcll(brf & ~bcL);
+                cu += __popcll((bsf | brf) & ~bcL);
+            }
         }
         minOld = wave_min(minOld);
         __syncthreads();
         T minNew = kInf;
         while (segStart < q && rem[segStart] == 0) ++segStart;
         for (int j = segStart; j < q; ++j) {
-            if (cs == 0 || cr == 0) break;               // no further pair can form at this t
+            // no further pair can form at this t: a pair needs a free send port and a free receive port on two
+            // different processors (a single processor left over with both ports free would otherwise be
+            // offered every remaining segment in vain)
+            if (cs == 0 || cr == 0 || cu < 2) break;
             int remj = rem[j];
             if (remj == 0) continue;                     // everybody has sent segment j
             const bool last = j == q - 1;
@@ -180,7 +198,7 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             const int l = sN < rN ? sN : rN;
             if (l == 0) continue;
             // ---- pass B: final send and receive sets (first l of each), word by word with running ranks
-            int carryF = 0, carryS = 0, carryR = 0;
+            int carryF = 0, carryS = 0, carryR = 0, gone = 0;
             for (int w0 = 0; w0 < W; w0 += kWave) {
                 const int w = w0 + lane;
                 const bool on = w < W;
@@ -199,8 +217,10 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                 if (on) {
                     sendSet[w] = sset; recvSet[w] = rset; prefS[w] = exS; prefR[w] = exR;
                     sent[static_cast<size_t>(j) * W + w] |= sset;
-                    sfree[w] &= ~sset;
-                    rfree[w] &= ~rset;
+                    const uint64_t sf0 = sfree[w], rf0 = rfree[w], open = ~compL[w];
+                    sfree[w] = sf0 & ~sset;
+                    rfree[w] = rf0 & ~rset;
+                    gone += __popcll((sf0 | rf0) & open) - __popcll(((sf0 & ~sset) | (rf0 & ~rset)) & open);
                 }
                 carryF += __shfl(incF, kWave - 1, kWave);
                 carryS += __shfl(incS, kWave - 1, kWave);
@@ -208,11 +228,18 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             }
             __syncthreads();
             // ---- pass C: bit sets -> index lists in ascending processor order
-            for (int w = 0; w < W; ++w) {
-                const uint64_t ss = sendSet[w], rs = recvSet[w];
-                if ((ss | rs) == 0) continue;
-                if ((ss >> lane) & 1) sendList[prefS[w] + rank_below(ss)] = w * kWave + lane;
-                if ((rs >> lane) & 1) recvList[prefR[w] + rank_below(rs)] = w * kWave + lane;
+            // (every lane looks at one word of 64, and only the words that hold a sender or receiver are expanded:
+            // with thousands of processors most words of a visit are empty)
+            for (int w0 = 0; w0 < W; w0 += kWave) {
+                const int wl = w0 + lane;
+                uint64_t some = ballot64(wl < W && (sendSet[wl] | recvSet[wl]) != 0);
+                while (some != 0) {
+                    const int w = w0 + __builtin_ctzll(some);
+                    some &= some - 1;
+                    const uint64_t ss = sendSet[w], rs = recvSet[w];
+                    if ((ss >> lane) & 1) sendList[prefS[w] + rank_below(ss)] = w * kWave + lane;
+                    if ((rs >> lane) & 1) recvList[prefR[w] + rank_below(rs)] = w * kWave + lane;
+                }
             }
             __syncthreads();
             // ---- pass D: entry-wise pairing
@@ -236,6 +263,7 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             if (tc < minNew) minNew = tc;
             if (tr < minNew) minNew = tr;
             cs -= l; cr -= l;
+            cu -= wave_sum(gone);
             remj -= l;
             if (lane == 0) rem[j] = remj;
             if (remj == 0) {                              // only the root is left: it finishes after the last arrival
