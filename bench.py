@@ -63,6 +63,9 @@ def cpu_baseline(host, seconds_hint=20.0):
 
 SEARCH_PROBLEMS = 10000
 
+# profiles/sweep100k_sq_instruction_counters.txt
+PROFILED_VALU_BUSY = {"simulate_uni": 0.31, "simulate_bi": 0.38, "schedule_uni": 0.18, "schedule_bi": 0.31}
+
 # per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
 PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 5.9e8, "schedule_uni": 9.11e10, "schedule_bi": 2.58e10,
                           "replay_i32": 4.33e9, "replay_f32": 4.33e9}
@@ -190,6 +193,9 @@ def main():
     # (FETCH_SIZE and WRITE_SIZE, scaled by what they read for a 1 GiB copy); None where not collected
     roof["traffic"] = PROFILED_TRAFFIC_BYTES.get(dominant)
     roof["kernel"] = dominant
+    # share of the chip's VALU issue slots the call's kernel uses, from the SQ counter run summarised under profiles/
+    # (SQ_INSTS_VALU x 4 cycles / (1024 SIMDs x launch time x 2.4 GHz)); None where not collected
+    roof["valu_busy_profiled"] = PROFILED_VALU_BUSY.get(dominant)
     replay_bytes = 4.0 * REPLAY_N * (REPLAY_P + 1)
     out = {
         "metric": "greedy schedules simulated/sec (uni+bi, p<=65536) + replay HBM GB/s vs peak",
