@@ -446,6 +446,20 @@ def test_unequal_segmentation_matches_the_oracle(prs, cost, limits, monkeypatch)
             assert _np(got[key])[i].item() == ref[key], (i, key)
 
 
+def test_unequal_segmentation_of_one_unit(prs):
+    """m_max = 1: one segmentation per problem, the unsegmented message, which is the binomial tree."""
+    p = np.array([2, 3, 17, 64, 1000], np.int32)
+    n = len(p)
+    host = prs_inputs.SweepConfigs(p, np.zeros(n, np.int32), np.ones(n, np.int64), np.full(n, 3, np.int64),
+                                   np.full(n, 2, np.int64), np.ones(n, np.int64), "i64")
+    got = prs.unequal_segmentation_batch(prs.DeviceConfigs.from_host(host), 1024, 1)
+    _sync()
+    want = np.array([math.ceil(math.log2(x)) * (3 + 2 + 1) for x in p])
+    assert np.array_equal(_np(got["T_all"])[:, 0], want) and np.array_equal(_np(got["T_best"]), want)
+    assert np.array_equal(_np(got["T_equi"]), want) and np.all(_np(got["n_best"]) == 1)
+    assert np.all(_np(got["equi_optimal"]) == 3) and np.all(_np(got["cuts_best"]) == 0)
+
+
 def test_unequal_segmentation_reproduces_table4(prs):
     """The paper's experiment at full size (m = 10, beta = 1, 29 values of alpha, gamma in {0, 1}, 17 values of
     p up to 1024: 986 problems x 512 segmentations) on the GPU, checked against the printed table: the same 61
