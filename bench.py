@@ -221,7 +221,24 @@ def main():
                                    "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
         "roofline": roof,
     }
-    # outside the timed step: the best-segmentation search (Sections 5.2, 6.1) over the sweep's first 10,000 problems,
+    # outside the timed step: what plain device kernels reach on the same 4 GiB of buffers (the practical ceilings
+    # next to the published 8 TB/s): a device-to-device copy (bytes read + bytes written) and a read-only pass
+    def timed(fn, reps=3):
+        best = float("inf")
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+    buf_bytes = 4.0 * REPLAY_P * REPLAY_N
+    buf_i.copy_(buf_f.view(i32))                                         # warm-up; buf_i is no longer needed
+    out["replay"]["device_copy_GBps"] = 2 * buf_bytes / (timed(lambda: buf_i.copy_(buf_f.view(i32))) * 1e-3) / 1e9
+    out["replay"]["device_read_GBps"] = buf_bytes / (timed(lambda: buf_f.max()) * 1e-3) / 1e9
+    # the best-segmentation search (Sections 5.2, 6.1) over the sweep's first 10,000 problems,
     # ten power-of-two segment counts each
     sub = prs.DeviceConfigs.from_host(host.take(np.arange(SEARCH_PROBLEMS)))
     search_ms = {}
