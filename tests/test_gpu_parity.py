@@ -297,6 +297,22 @@ def test_large_p_sample(prs, model):
     assert np.all(_np(got["cfg_status"]) == 0)
 
 
+@pytest.mark.parametrize("model", [0, 1])
+def test_schedules_beyond_1024_processors(prs, model):
+    """Full schedules where the per-processor state no longer fits the small-machine kernels (bi-greedy: one
+    wavefront per configuration with bit sets of many words; uni-greedy: streams far longer than the LDS ring),
+    integer and fp64 costs, equal and ragged last segments."""
+    p = np.array([1025, 2000, 3001, 1500], np.int32)
+    q = np.array([3, 2, 5, 4], np.int32)
+    m = np.array([9, 7, 20, 4], np.int64)
+    host = prs_inputs.SweepConfigs(p, q, m, np.array([3, 0, 7, 2], np.int64), np.array([1, 2, 1, 3], np.int64),
+                                   np.array([1, 1, 0, 2], np.int64), "i64")
+    _check_schedules(prs, host, model, 4096, 8)
+    hostf = prs_inputs.SweepConfigs(p[:3], q[:3], m[:3] * 1000 + 1, np.array([2e-6, 1e-5, 3e-6]), np.array([1e-9, 2e-9, 5e-10]),
+                                    np.array([1e-10, 0.0, 3e-10]), "f64")
+    _check_schedules(prs, hostf, model, 4096, 8)
+
+
 # --------------------------------------------------------------------------- best segmentation per algorithm
 @pytest.mark.parametrize("model", [0, 1])
 @pytest.mark.parametrize("cost", ["i64", "f64"])
