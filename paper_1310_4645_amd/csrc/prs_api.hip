@@ -114,6 +114,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.limits.q = kGroupQMax;
     L.limits.by_work = 0;
     for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = 0;
+    L.limits.giant_log2 = kGiantLog2;
     static const int group_lpc[kClasses - 1] = {1, 4, 16};
     if (model == PRS_UNI) {
         // classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one launch,
@@ -121,10 +122,13 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         L.limits.by_work = 1;
         for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kUniWork[k];
         // tuning and test knob: "a,b,c" replaces the three limits (0,0,0 sends everything to the largest groups)
+        // (a fourth value replaces the binary logarithm of the pair count from which a configuration gets a whole wavefront)
         if (const char *env = getenv("PRS_UNI_GROUP_WORK")) {
-            long long a = 0, b = 0, c3 = 0;
-            if (sscanf(env, "%lld,%lld,%lld", &a, &b, &c3) == 3 && a >= 0 && b >= a && c3 >= b) {
+            long long a = 0, b = 0, c3 = 0, g = kGiantLog2;
+            const int got = sscanf(env, "%lld,%lld,%lld,%lld", &a, &b, &c3, &g);
+            if (got >= 3 && a >= 0 && b >= a && c3 >= b) {
                 L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3;
+                if (got == 4 && g >= 0 && g < kWorkBuckets) L.limits.giant_log2 = static_cast<int32_t>(g);
             }
         }
         for (int k = 0; k < kClasses; ++k) {

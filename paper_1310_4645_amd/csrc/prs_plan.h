@@ -18,7 +18,13 @@ struct PlanHeader {
     int32_t hist[kClasses * kWorkBuckets];
     int32_t start[kClasses * kWorkBuckets];
     int32_t cursor[kClasses * kWorkBuckets];
+    // The heaviest configurations of the last class (at least 2^giant_log2 pairs) come first in its order; the
+    // uni-greedy kernels run them on whole wavefronts and draw them from a ticket counter of their own.
+    int32_t giant_count;
+    unsigned long long ticket_giant;
 };
+constexpr int kGiantLog2 = 23;
+enum ClassPart { kWholeClass = 0, kGiantPart = 1, kRestPart = 2 };
 
 // By size (by_work == 0): class k holds p <= limits.p[k]; the last class the rest and every configuration
 // with more than q segments.
@@ -28,6 +34,7 @@ struct ClassLimits {
     int32_t q;
     int32_t by_work;
     int64_t work[kClasses - 1];
+    int32_t giant_log2;          // configurations of the last class with at least 2^giant_log2 pairs are "giant"
 };
 
 struct PlanLaunch {

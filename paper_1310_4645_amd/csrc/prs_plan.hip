@@ -26,6 +26,7 @@ __global__ void plan_clear(PlanHeader *h)
 {
     const int i = threadIdx.x;
     if (i < kClasses + 1) { h->ticket[i] = 0ULL; h->class_begin[i] = 0; h->class_count[i] = 0; }
+    if (i == 0) { h->giant_count = 0; h->ticket_giant = 0ULL; }
     for (int k = i; k < kClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
 }
 
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_hist(ConfigArrays cfg, int6
         if (local[k] != 0) atomicAdd(&h->hist[k], local[k]);
 }
 
-__global__ void plan_scan(PlanHeader *h)
+__global__ void plan_scan(PlanHeader *h, int32_t giant_log2)
 {
     if (threadIdx.x != 0) return;
     int32_t run = 0;
@@ -61,6 +62,9 @@ __global__ void plan_scan(PlanHeader *h)
         }
         h->class_count[c] = run - h->class_begin[c];
     }
+    int32_t giants = 0;                                   // buckets are ordered heaviest first: bucket b holds floor(log2) = kWorkBuckets-1-b
+    for (int b = 0; b <= kWorkBuckets - 1 - giant_log2; ++b) giants += h->hist[(kClasses - 1) * kWorkBuckets + b];
+    h->giant_count = giants;
 }
 
 template <typename T>
@@ -90,11 +94,11 @@ hipError_t launch_plan(const PlanLaunch &L)
     hipLaunchKernelGGL(plan_clear, dim3(1), dim3(256), 0, L.stream, L.header);
     if (L.cost == PRS_COST_I64) {
         hipLaunchKernelGGL((plan_hist<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
-        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2);
         hipLaunchKernelGGL((plan_scatter<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     } else {
         hipLaunchKernelGGL((plan_hist<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
-        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2);
         hipLaunchKernelGGL((plan_scatter<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     }
     return hipGetLastError();

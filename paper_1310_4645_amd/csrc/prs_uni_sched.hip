@@ -38,8 +38,8 @@ template <typename T> __device__ __forceinline__ bool key_less(T xa, int32_t ia,
 
 template <typename T, int G>
 __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays &cfg, int32_t p_max, int32_t q_max,
-                                               const SchedOut &sched, PlanHeader *plan, const int32_t *order, int cls, char *slot,
-                                               int32_t slot_p)
+                                               const SchedOut &sched, PlanHeader *plan, const int32_t *order, int cls, int part,
+                                               char *slot, int32_t slot_p)
 {
     constexpr int M = kRingS - 1;
     T *ringX = reinterpret_cast<T *>(lds_raw);                                   // [kRingS][64] stream values
@@ -57,7 +57,11 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
         return reinterpret_cast<int32_t *>(slot + l * per_lane + 2 * static_cast<size_t>(slot_p) * 8 + static_cast<size_t>(par) * slot_p * 4);
     };
     int32_t *bufB = reinterpret_cast<int32_t *>(slot + lane * per_lane + 2 * static_cast<size_t>(slot_p) * 12);
-    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    // part of the class this pass works on: all of it, its giant configurations only, or the rest after those
+    int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    unsigned long long *tickets = &plan->ticket[cls];
+    if (part == kGiantPart) { count = plan->giant_count; tickets = &plan->ticket_giant; }
+    else if (part == kRestPart) { begin += plan->giant_count; count -= plan->giant_count; }
     const T kInf = CostTraits<T>::inf();
 
     // ---- per-group state (the same in all lanes of a group)
@@ -91,7 +95,7 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
     for (;;) {
         // ---------------------------------------------------------------- fetch a configuration
         if (!have && !exhausted) {
-            unsigned long long got = atomicAdd(&plan->ticket[cls], gl == 0 ? 1ULL : 0ULL);
+            unsigned long long got = atomicAdd(tickets, gl == 0 ? 1ULL : 0ULL);
             int64_t ticket = static_cast<int64_t>(got);
             if (G > 1) {
                 const uint32_t lo = __shfl(static_cast<uint32_t>(got), 0, G), hi = __shfl(static_cast<uint32_t>(got >> 32), 0, G);
@@ -352,13 +356,15 @@ __global__ __launch_bounds__(kWave) void uni_sched_kernel(ConfigArrays cfg, int3
 {
     PRS_DYNAMIC_LDS(lds_raw);
     char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
-    uni_sched_body<T, 32>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, slot, slot_p);
+    uni_sched_body<T, 64>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, kGiantPart, slot, slot_p);
     __syncthreads();
-    uni_sched_body<T, 16>(lds_raw, cfg, p_max, q_max, sched, plan, order, 2, slot, slot_p);
+    uni_sched_body<T, 32>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, kRestPart, slot, slot_p);
     __syncthreads();
-    uni_sched_body<T, 4>(lds_raw, cfg, p_max, q_max, sched, plan, order, 1, slot, slot_p);
+    uni_sched_body<T, 16>(lds_raw, cfg, p_max, q_max, sched, plan, order, 2, kWholeClass, slot, slot_p);
     __syncthreads();
-    uni_sched_body<T, 1>(lds_raw, cfg, p_max, q_max, sched, plan, order, 0, slot, slot_p);
+    uni_sched_body<T, 4>(lds_raw, cfg, p_max, q_max, sched, plan, order, 1, kWholeClass, slot, slot_p);
+    __syncthreads();
+    uni_sched_body<T, 1>(lds_raw, cfg, p_max, q_max, sched, plan, order, 0, kWholeClass, slot, slot_p);
 }
 
 hipError_t launch_uni_sched(const UniLaunch &L)

@@ -41,8 +41,8 @@ size_t uni_times_slot_bytes(int32_t p_cap) { return static_cast<size_t>(kWave) *
 // and a smaller last one; every lane keeps the part of the composition that starts at its segment.
 template <typename T, int G, bool kComp>
 __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg, int32_t p_max, int32_t q_max, int model,
-                                               const TimesOut &times, PlanHeader *plan, const int32_t *order, int cls, T *slot,
-                                               int32_t slot_p)
+                                               const TimesOut &times, PlanHeader *plan, const int32_t *order, int cls, int part,
+                                               T *slot, int32_t slot_p)
 {
     constexpr int M = kRing - 1;
     const int lane = lane_id(), gl = lane & (G - 1), gbase = lane & ~(G - 1);
@@ -50,7 +50,11 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
     const uint64_t gmask = (G == 64 ? ~UINT64_C(0) : ((UINT64_C(1) << G) - 1)) << gbase;
     T *mybuf = slot + static_cast<size_t>(lane) * 2 * slot_p;       // [2][slot_p]
     const T *prodbuf = slot + static_cast<size_t>(prod) * 2 * slot_p;
-    const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    // part of the class this pass works on: all of it, its giant configurations only, or the rest after those
+    int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
+    unsigned long long *tickets = &plan->ticket[cls];
+    if (part == kGiantPart) { count = plan->giant_count; tickets = &plan->ticket_giant; }
+    else if (part == kRestPart) { begin += plan->giant_count; count -= plan->giant_count; }
     const T kInf = CostTraits<T>::inf();
 
     // ---- per-group state (the same in all lanes of a group)
@@ -74,7 +78,7 @@ __device__ __forceinline__ void uni_times_body(T *ring, const ConfigArrays &cfg,
     for (;;) {
         // ---------------------------------------------------------------- fetch a configuration
         if (!have && !exhausted) {
-            unsigned long long got = atomicAdd(&plan->ticket[cls], gl == 0 ? 1ULL : 0ULL);
+            unsigned long long got = atomicAdd(tickets, gl == 0 ? 1ULL : 0ULL);
             int64_t ticket = static_cast<int64_t>(got);
             if (G > 1) {
                 const uint32_t lo = __shfl(static_cast<uint32_t>(got), 0, G), hi = __shfl(static_cast<uint32_t>(got >> 32), 0, G);
@@ -226,13 +230,16 @@ __global__ __launch_bounds__(kWave) void uni_times_kernel(ConfigArrays cfg, int3
     PRS_DYNAMIC_LDS(lds_raw);
     T *ring = reinterpret_cast<T *>(lds_raw);                    // [kRing][64]
     T *slot = reinterpret_cast<T *>(slots + static_cast<size_t>(blockIdx.x) * slot_bytes);
-    uni_times_body<T, 32, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, slot, slot_p);
+    // configurations of millions of pairs trail their predecessor segment by thousands of entries: a whole wavefront each
+    uni_times_body<T, 64, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, kGiantPart, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 16, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 2, slot, slot_p);
+    uni_times_body<T, 32, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, kRestPart, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 4, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 1, slot, slot_p);
+    uni_times_body<T, 16, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 2, kWholeClass, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 1, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 0, slot, slot_p);
+    uni_times_body<T, 4, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 1, kWholeClass, slot, slot_p);
+    __syncthreads();
+    uni_times_body<T, 1, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 0, kWholeClass, slot, slot_p);
 }
 
 template <typename T, bool kComp>

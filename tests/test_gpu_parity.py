@@ -121,10 +121,12 @@ def test_integer_costs_ragged_segments_and_larger_p(prs, model):
     _check_schedules(prs, host, model, 256, 32)
 
 
-@pytest.mark.parametrize("limits", ["0,0,0", "0,0,1000000000", "0,1000000000,1000000000", "1000000000,1000000000,1000000000"])
+@pytest.mark.parametrize("limits", ["0,0,0,0", "0,0,0,10", "0,0,0", "0,0,1000000000", "0,1000000000,1000000000",
+                                    "1000000000,1000000000,1000000000"])
 def test_uni_every_group_size(prs, limits, monkeypatch):
-    """Uni-greedy runs a configuration on 32, 16, 4 or 1 lanes depending on its number of pairs; here every
-    group size gets the same mixed batch (integer and fp64 costs, with fp64 rounding collisions)."""
+    """Uni-greedy runs a configuration on 64, 32, 16, 4 or 1 lanes depending on its number of pairs; here every
+    group size gets the same mixed batch (integer and fp64 costs, with fp64 rounding collisions).  A fourth
+    limit is the binary logarithm of the pair count from which a configuration gets all 64 lanes."""
     monkeypatch.setenv("PRS_UNI_GROUP_WORK", limits)
     rng = np.random.default_rng(77)
     n = 96
@@ -421,7 +423,7 @@ def test_theoretical_experiment_bidirectional_section_6_1(prs):
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 
 
-@pytest.mark.parametrize("limits", [None, "0,0,0", "0,0,1000000000", "0,1000000000,1000000000"])
+@pytest.mark.parametrize("limits", [None, "0,0,0,0", "0,0,0", "0,0,1000000000", "0,1000000000,1000000000"])
 @pytest.mark.parametrize("cost", ["i64", "f64"])
 def test_unequal_segmentation_matches_the_oracle(prs, cost, limits, monkeypatch):
     """Every segmentation of short messages of mixed length through uni-greedy, at every group size: all
