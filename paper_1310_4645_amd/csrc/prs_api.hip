@@ -77,7 +77,7 @@ enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
-constexpr int64_t kUniWork[kClasses - 1] = {2048, 16384, 131072};   // most pairs of a configuration run by 1, 4, 16 lanes
+constexpr int64_t kUniWork[kClasses - 1] = {1024, 8192, 262144};   // most pairs of a configuration run by 1, 4, 16 lanes
 
 struct ClassSpec {
     ClassKind kind;
