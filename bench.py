@@ -64,10 +64,10 @@ def cpu_baseline(host, seconds_hint=20.0):
 SEARCH_PROBLEMS = 10000
 
 # profiles/sweep100k_sq_instruction_counters.txt
-PROFILED_VALU_BUSY = {"simulate_uni": 0.31, "simulate_bi": 0.38, "schedule_uni": 0.18, "schedule_bi": 0.31}
+PROFILED_VALU_BUSY = {"simulate_uni": 0.32, "simulate_bi": 0.36, "schedule_uni": 0.20, "schedule_bi": 0.30}
 
 # per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
-PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.03e10, "simulate_bi": 5.9e8, "schedule_uni": 9.11e10, "schedule_bi": 2.58e10,
+PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.02e10, "simulate_bi": 5.8e8, "schedule_uni": 8.80e10, "schedule_bi": 2.58e10,
                           "replay_i32": 4.33e9, "replay_f32": 4.33e9}
 
 
