@@ -169,6 +169,8 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
                 c.lds = true;
                 c.lds_bitmap_bytes = static_cast<int32_t>(bitmap < kBitmapLdsMax ? bitmap : kBitmapLdsMax);
                 c.lds_bytes = small + static_cast<size_t>(c.lds_bitmap_bytes);
+            } else if (bi_masks_bytes(c.p_cap) <= kLdsPerBlockMax) {
+                c.lds_bytes = bi_masks_bytes(c.p_cap);             // bit sets in LDS, lists and counters in the slot
             }
             c.slot_bytes = bi_slot_bytes(c.p_cap, q_max, c.lds);
         }

@@ -39,7 +39,7 @@ __host__ __device__ inline BiSmall bi_small_layout(int32_t p_cap, int32_t q_cap)
     const size_t p = static_cast<size_t>(p_cap), q = static_cast<size_t>(q_cap);
     L.W = static_cast<int>((p + 63) / 64);
     size_t o = 0;
-    L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 9);   // 9 word arrays
+    L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 6);   // 6 word arrays
     L.pref = o; o += bi_align(static_cast<size_t>(L.W) * 4 * 2);
     L.sendList = o; o += bi_align((p / 2 + 1) * 4);
     L.recvList = o; o += bi_align((p / 2 + 1) * 4);
@@ -65,6 +65,9 @@ __host__ __device__ inline BiBig bi_big_layout(int32_t p_cap)
 }
 
 size_t bi_small_bytes(int32_t p_cap, int32_t q_cap) { return bi_small_layout(p_cap, q_cap).total; }
+// The bit sets and list positions alone (the first two arrays of the small layout): what every pass of a visit
+// reads and writes.  They can sit in LDS when the lists and counters no longer fit beside them.
+size_t bi_masks_bytes(int32_t p_cap) { return bi_small_layout(p_cap, 1).sendList; }
 __host__ __device__ inline size_t bi_bitmap_size(int32_t p_cap, int32_t q_cap)
 {
     return bi_align(static_cast<size_t>((p_cap + 63) / 64) * static_cast<size_t>(q_cap) * 8);
@@ -77,6 +80,7 @@ size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds)
 
 struct BiState {
     char *small;         // BiSmall arrays (LDS or slot)
+    char *masks;         // the bit sets and list positions of BiSmall, if they are kept apart from the rest (LDS); else null
     char *big;           // BiBig arrays (slot)
     uint64_t *sent;      // [q][W] bitmap (LDS if it fits, else slot)
     int Wcap;            // words per mask array as laid out
@@ -94,12 +98,12 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
     T *R = reinterpret_cast<T *>(bs.big + bs.bl.R);
     T *C1 = reinterpret_cast<T *>(bs.big + bs.bl.C1);
     int32_t *nsent = reinterpret_cast<int32_t *>(bs.big + bs.bl.nsent);
-    uint64_t *mk = reinterpret_cast<uint64_t *>(bs.small + bs.sl.masks);
+    char *mbase = bs.masks ? bs.masks : bs.small;       // masks and pref have the same offsets in either place
+    uint64_t *mk = reinterpret_cast<uint64_t *>(mbase + bs.sl.masks);
     const int Wc = bs.Wcap;
     uint64_t *sfree = mk, *rfree = mk + Wc, *compF = mk + 2 * Wc, *compL = mk + 3 * Wc;
-    uint64_t *soW = mk + 4 * Wc, *roW = mk + 5 * Wc, *frW = mk + 6 * Wc;
-    uint64_t *sendSet = mk + 7 * Wc, *recvSet = mk + 8 * Wc;
-    int32_t *prefS = reinterpret_cast<int32_t *>(bs.small + bs.sl.pref), *prefR = prefS + Wc;
+    uint64_t *sendSet = mk + 4 * Wc, *recvSet = mk + 5 * Wc;
+    int32_t *prefS = reinterpret_cast<int32_t *>(mbase + bs.sl.pref), *prefR = prefS + Wc;
     int32_t *sendList = reinterpret_cast<int32_t *>(bs.small + bs.sl.sendList);
     int32_t *recvList = reinterpret_cast<int32_t *>(bs.small + bs.sl.recvList);
     int32_t *rem = reinterpret_cast<int32_t *>(bs.small + bs.sl.rem);
@@ -178,7 +182,6 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                     const uint64_t comp = last ? compL[w] : compF[w];
                     const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w];
                     const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
-                    soW[w] = so; roW[w] = ro; frW[w] = fr;
                     ns_ += __popcll(so); nr_ += __popcll(ro); nf_ += __popcll(fr);
                 }
             }
@@ -202,7 +205,15 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             for (int w0 = 0; w0 < W; w0 += kWave) {
                 const int w = w0 + lane;
                 const bool on = w < W;
-                const uint64_t fr = on ? frW[w] : 0, so = on ? soW[w] : 0, ro = on ? roW[w] : 0;
+                uint64_t fr = 0, so = 0, ro = 0;                          // the three lists of pass A again (nothing has changed)
+                if (on) {
+                    uint64_t valid = ~UINT64_C(0);
+                    if (w == W - 1 && (p & 63)) valid = (UINT64_C(1) << (p & 63)) - 1;
+                    const uint64_t memb = ~sent[static_cast<size_t>(j) * W + w] & valid;
+                    const uint64_t comp = last ? compL[w] : compF[w];
+                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w];
+                    fr = sOK & rOK; so = sOK ^ fr; ro = rOK ^ fr;
+                }
                 const int pf = __popcll(fr);
                 const int incF = wave_inclusive_scan(pf);
                 const int exF = carryF + incF - pf;                       // free-list rank of this word's first entry
@@ -280,7 +291,9 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
     return Tmax;
 }
 
-template <typename T, bool kSched, bool kLds>
+// kPlace: 0 = all arrays of a configuration in its workspace slot, 1 = the small arrays (and, if it fits, the sent
+// bitmap) in LDS, 2 = only the bit sets and list positions in LDS (tens of thousands of processors).
+template <typename T, bool kSched, int kPlace>
 __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model, TimesOut times,
                                                    SchedOut sched, PlanHeader *plan, const int32_t *order, int cls,
                                                    int32_t state_p, int32_t state_q, int32_t lds_bitmap_bytes, char *slots,
@@ -295,7 +308,9 @@ __global__ __launch_bounds__(kWave) void bi_kernel(ConfigArrays cfg, int32_t p_m
     bs.Wcap = bs.sl.W;
     bs.big = slot;
     uint64_t *slot_bitmap = reinterpret_cast<uint64_t *>(slot + bs.bl.total);
+    constexpr bool kLds = kPlace == 1;
     bs.small = kLds ? lds_raw : slot + bs.bl.total + bi_bitmap_size(state_p, state_q);
+    bs.masks = kPlace == 2 ? lds_raw : nullptr;
     uint64_t *lds_bitmap = reinterpret_cast<uint64_t *>(lds_raw + bs.sl.total);
     const int32_t count = plan->class_count[cls], begin = plan->class_begin[cls];
     for (;;) {
@@ -332,11 +347,14 @@ template <typename T, bool kSched>
 static hipError_t launch_bi_t(const BiLaunch &L)
 {
     if (L.lds_p > 0)
-        hipLaunchKernelGGL((bi_kernel<T, kSched, true>), dim3(L.grid), dim3(kWave), L.lds_bytes, L.stream, L.cfg, L.p_max, L.q_max,
+        hipLaunchKernelGGL((bi_kernel<T, kSched, 1>), dim3(L.grid), dim3(kWave), L.lds_bytes, L.stream, L.cfg, L.p_max, L.q_max,
                            L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slot_q, L.lds_bitmap_bytes, L.slots,
                            L.slot_bytes);
+    else if (L.lds_bytes > 0)                                     // the caller sized it with bi_masks_bytes(slot_p)
+        hipLaunchKernelGGL((bi_kernel<T, kSched, 2>), dim3(L.grid), dim3(kWave), L.lds_bytes, L.stream, L.cfg, L.p_max, L.q_max,
+                           L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slot_q, 0, L.slots, L.slot_bytes);
     else
-        hipLaunchKernelGGL((bi_kernel<T, kSched, false>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.p_max, L.q_max,
+        hipLaunchKernelGGL((bi_kernel<T, kSched, 0>), dim3(L.grid), dim3(kWave), 0, L.stream, L.cfg, L.p_max, L.q_max,
                            L.model, L.times, L.sched, L.plan, L.order, L.cls, L.slot_p, L.slot_q, 0, L.slots, L.slot_bytes);
     return hipGetLastError();
 }

@@ -46,6 +46,7 @@ typedef UniLaunch BiLaunch;   // same fields; slots sized by bi_slot_bytes
 
 size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lists, per-segment counters
 size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
+size_t bi_masks_bytes(int32_t p_cap);                              // the bit sets and list positions among the small arrays
 size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
 // Several configurations per wavefront (p <= 1024, q <= 1023): 1, 4 or 16 lanes per configuration
 // (plan classes 0, 1, 2), all three in one launch of one resident set of blocks.  start[k] blocks begin with
