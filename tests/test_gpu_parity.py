@@ -310,6 +310,7 @@ def test_schedules_beyond_1024_processors(prs, model):
     host = prs_inputs.SweepConfigs(p, q, m, np.array([3, 0, 7, 2], np.int64), np.array([1, 2, 1, 3], np.int64),
                                    np.array([1, 1, 0, 2], np.int64), "i64")
     _check_schedules(prs, host, model, 4096, 8)
+    _check_schedules(prs, host, model, 40000, 8)      # sized for tens of thousands of processors: other placement of the state
     hostf = prs_inputs.SweepConfigs(p[:3], q[:3], m[:3] * 1000 + 1, np.array([2e-6, 1e-5, 3e-6]), np.array([1e-9, 2e-9, 5e-10]),
                                     np.array([1e-10, 0.0, 3e-10]), "f64")
     _check_schedules(prs, hostf, model, 4096, 8)
