@@ -326,3 +326,32 @@ def unequal_segmentation(p, m, alpha, beta, gamma, cost="i64"):
     wide = any(all(x == comps[i][0] for x in comps[i][:-1]) and comps[i][-1] <= comps[i][0] for i in winners)
     return dict(T_all=np.array(T_all), T_best=T_best, cuts_best=winners[0], n_best=len(winners), T_equi=T_equi,
                 cuts_equi=cuts_equi, equi_optimal=(1 if T_equi == T_best else 0) | (2 if wide else 0))
+
+
+def butterfly_threshold_closed_form(p: int) -> float:
+    """Section 6.1 (the figure of parameters for which the butterfly can beat the reversed optimal broadcast, i.e.
+    bi-greedy): the largest beta/gamma for which some message size lets the butterfly win, with the segment count
+    treated as a real number.  From Table III, with L = ceil(log2 p): the broadcast-based time at its best
+    segment size is (sqrt((L-1) alpha) + sqrt((beta+gamma) m))^2, the butterfly's is
+    2 L alpha + (2 beta + gamma)(p-1)/p m.  Their difference is A + B x^2 - C x in x = sqrt(m) with
+    A = (L+1) alpha, B = beta (p-2)/p - gamma/p, C = 2 sqrt((L-1) alpha (beta+gamma)); it is negative for some
+    x exactly when C^2 > 4 A B, in which alpha cancels:
+        (L-1)(beta+gamma) > (L+1)(beta (p-2)/p - gamma/p).
+    Solved for beta/gamma this gives the value returned.  (p >= 4.)"""
+    L = ceil_log2(p)
+    return ((L - 1) + (L + 1) / p) / ((L + 1) * (p - 2) / p - (L - 1))
+
+
+def butterfly_wins_somewhere(p, alpha, beta, gamma, m_values, q_max) -> bool:
+    """True if for one of the message sizes the butterfly's time (Table III) is below the reversed optimal
+    broadcast's time at the best of the segment counts 1..q_max, each tried in turn."""
+    for m in m_values:
+        best, butterfly = None, None
+        for q_req in range(1, min(q_max, m) + 1):
+            q, sz, _ = segmentation(m, q_req)
+            cf = closed_forms(BI, p, q, m, sz, alpha, beta, gamma, "f64")
+            butterfly = cf["butterfly"]
+            best = cf["revopt"] if best is None or cf["revopt"] < best else best
+        if butterfly < best:
+            return True
+    return False

@@ -420,6 +420,38 @@ def test_theoretical_experiment_bidirectional_section_6_1(prs):
         assert np.array_equal(_np(best["q_" + key])[idx], ref["q_" + key]), key
 
 
+@pytest.mark.parametrize("p", [64, 1024])
+def test_butterfly_threshold_by_bisection(prs, p):
+    """Section 6.1: the largest beta/gamma for which some message size lets the butterfly beat the reversed
+    optimal broadcast (= bi-greedy), found by bisection over the library's closed forms (every segment count
+    1..512 for message sizes 2^4..2^22), takes the same steps as the bisection over the oracle's closed forms,
+    stays below 5 and within a tenth of the closed form of the line."""
+    ms = [2 ** k for k in range(4, 23)]
+    mq = [(m, q) for m in ms for q in range(1, min(512, m) + 1)]
+    n = len(mq)
+    m_arr = np.array([x[0] for x in mq], np.int64)
+    q_arr = np.array([x[1] for x in mq], np.int32)
+    first = np.concatenate([[0], np.nonzero(np.diff(m_arr))[0] + 1])          # where each message size starts
+
+    def wins_on_gpu(r):
+        host = prs_inputs.SweepConfigs(np.full(n, p, np.int32), q_arr, m_arr, np.full(n, 1000.0), np.full(n, r), np.ones(n), "f64")
+        got = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(host), prs.PRS_BI, 1024, 512)
+        _sync()
+        rev, bf = _np(got["revopt"]), _np(got["butterfly"])
+        best = np.minimum.reduceat(rev, first)
+        return bool(np.any(bf[first] < best))
+
+    lo_g = lo_o = 0.25
+    hi_g = hi_o = 16.0
+    for _ in range(8):
+        mid = math.sqrt(lo_g * hi_g)
+        lo_g, hi_g = (mid, hi_g) if wins_on_gpu(mid) else (lo_g, mid)
+        mid = math.sqrt(lo_o * hi_o)
+        lo_o, hi_o = (mid, hi_o) if O.butterfly_wins_somewhere(p, 1000.0, mid, 1.0, ms, 512) else (lo_o, mid)
+    assert (lo_g, hi_g) == (lo_o, hi_o)
+    assert hi_g < 5 and abs(math.sqrt(lo_g * hi_g) / O.butterfly_threshold_closed_form(p) - 1) < 0.1
+
+
 # --------------------------------------------------------------------------- unequal segmentation (Section 8)
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 

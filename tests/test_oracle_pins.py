@@ -479,6 +479,28 @@ def test_replay_of_baseline_trees_has_their_association():
             assert np.array_equal(O.replay(pp, off, *tree(pp, q), bi), bi.sum(axis=0, dtype=np.int64).astype(np.int32))
 
 
+def test_butterfly_can_only_win_for_small_beta_over_gamma():
+    """Section 6.1: below a line in the (p, beta/gamma) plane some message size lets the butterfly beat bi-greedy,
+    above it never; "for up to 1000 processors the ratio would have to be less than 5".  The closed form of the
+    line (segment count as a real number) stays below 5 up to 1024 processors and grows with p from 16 on; trying
+    message sizes and segment counts one by one lands within a tenth of it; the machine of Figure 6 (ratio 6)
+    is above the line for 64 processors, a ratio of 1 is below it."""
+    line = {p: O.butterfly_threshold_closed_form(p) for p in [4, 8, 16, 32, 64, 128, 256, 512, 1000, 1024]}
+    assert all(0 < r < 5 for r in line.values()) and line[1024] > 4.5
+    assert all(line[a] < line[b] for a, b in zip([16, 32, 64, 128, 256, 512], [32, 64, 128, 256, 512, 1000]))
+    ms = [2 ** k for k in range(4, 23)]
+    for p in (16, 64):
+        lo, hi = 0.25, 16.0
+        for _ in range(10):
+            mid = math.sqrt(lo * hi)
+            lo, hi = (mid, hi) if O.butterfly_wins_somewhere(p, 1000.0, mid, 1.0, ms, 512) else (lo, mid)
+        assert abs(math.sqrt(lo * hi) / line[p] - 1) < 0.1, (p, lo, hi, line[p])
+    assert not O.butterfly_wins_somewhere(64, 50000.0, 6.0, 1.0, [2 ** k for k in range(10, 28)], 512)
+    assert O.butterfly_wins_somewhere(64, 50000.0, 1.0, 1.0, [2 ** k for k in range(10, 28)], 512)
+    # alpha drops out of the condition
+    assert O.butterfly_wins_somewhere(64, 10.0, 2.0, 1.0, ms, 512) and O.butterfly_wins_somewhere(64, 1e5, 2.0, 1.0, [2 ** k for k in range(4, 30)], 4096)
+
+
 # --------------------------------------------------------------------------- best segmentation (Sections 5.2, 6.1)
 def _table1_pipeline_uni(p, q, m, a, b, g):
     sz = -(-m // q)
