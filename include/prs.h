@@ -138,9 +138,8 @@ int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Executes one schedule on data (Section 4: "after a receiving processor
- * receives a segment it will combine its segment with the segment
- * received"): with buf_i = in + i*stride_elems (i < p, n_elems values each),
+ * Executes one schedule on data (Section 4: the receiver of a pair combines
+ * the segment that arrived with its own copy of it): with buf_i = in + i*stride_elems (i < p, n_elems values each),
  * applying buf_dst[segment] = buf_dst[segment] + buf_src[segment] pair by
  * pair in the order given leaves the reduction in buf_0; that result, with
  * exactly that association of the additions, is written to out (n_elems

@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_HERE, "_build", "libprs_oracle.so")
 _lib = None
 
 UNI, BI = 0, 1
-MODE_LITERAL, MODE_EVENT, MODE_PRUNE = 0, 1, 2
+MODE_LITERAL, MODE_EVENT, MODE_PRUNE, MODE_LISTING_ONLY = 0, 1, 2, 4
 
 
 def build(force: bool = False) -> str:

@@ -24,14 +24,22 @@
  *    (C1 <= t < C2) or when a communication of length tcomm(j) started now
  *    would run into a computation that is already scheduled
  *    (t < C1 < t + tcomm(j)); the printed second clause has no guard.
+ *  - Algorithm 2 with a smaller last segment (Section 2 allows one): a
+ *    processor does not receive a segment whose combine would begin while
+ *    its own, longer send is still running -- Section 2 forbids
+ *    communication to overlap computation and the listing only guards the
+ *    other direction.  No effect when all segments are equal.
+ *  - Algorithm 2, comparisons of t + tcomm(j) with the end of an earlier
+ *    transfer of a segment of the same size: decided by the start times.
  *  - Algorithm 2: the root is never a sender (Lemma 1 (ii)); the printed
  *    sendProc does not exclude it.
  *  - Algorithm 2: lists are in ascending processor index (set semantics);
  *    the first l entries of each are paired entry by entry.
  *  - Algorithm 2: "M(i,j) = 0" as "has not sent" is kept as a separate flag.
  *  - Algorithm 2 assumes a unit time step; for real-valued costs t advances
- *    to the next time a port frees.  Both advances are implemented and
- *    compared in the tests.
+ *    to the next time a port frees or a processor held back by the Section 2
+ *    exclusion becomes eligible.  Both advances are implemented and compared
+ *    in the tests.
  *  - Table III, bidirectional binary: 2(N+q-2) rounds (see orc_closed_forms).
  *
  * Pins: see tests/test_oracle_*.py.  Parity unpinned: the processor
@@ -199,8 +207,8 @@ int64_t orc_exhaustive_uni_i64(int32_t p, int32_t q, const int64_t *sizes, int64
 }
 
 /* ------------------------------------------------------------------------
- * Replay of a schedule on data (Section 4: "after a receiving processor
- * receives a segment it will combine its segment with the segment received").
+ * Replay of a schedule on data (Section 4: the receiver of a pair combines
+ * the segment that arrived with its own copy of that segment).
  * buf holds p rows of n_elems values and is updated in place, pair by pair in
  * emission order: buf[dst][segment] = buf[dst][segment] + buf[src][segment].
  * seg_elem_offset[q+1] gives each segment's element range.  The reduction

@@ -309,18 +309,79 @@ def test_bi_time_advance_and_pruning_do_not_change_results():
                 assert np.array_equal(getattr(s, f), getattr(ref, f)), (p, list(sizes), a, b, g, mode, f)
 
 
-def test_bi_ragged_last_segment_schedule_is_consistent():
-    # Algorithm 2 is stated for equi-segmentation; with a smaller last segment everything but the
-    # no-overlap rule between a send and a later-scheduled combine still holds.
+def test_bi_ragged_last_segment_is_valid_and_sandwiched():
+    """Section 2 allows a smaller last segment and forbids communication to overlap computation.  Every such
+    schedule passes the validator with all rules on, and its time lies between two round counts: the root
+    takes the q segments in one after the other and the segment it takes in last still needs ceil(log2 p)
+    rounds of its own size (the bound of Table III's broadcast-based row, turned round, with each segment's
+    own round time): (q-1) r + L r_last <= T; and T <= (L+q-2) r + L r_last, the first q-1 segments run to
+    completion as Table III says and the last one after them on its own (an observation on this oracle, not a
+    statement of the paper)."""
     rng = np.random.default_rng(3)
-    for _ in range(60):
-        p = int(rng.integers(2, 30)); m = int(rng.integers(2, 50)); qr = int(rng.integers(2, 9))
-        a, b, g = int(rng.integers(0, 6)), int(rng.integers(1, 3)), int(rng.integers(0, 3))
+    seen = 0
+    for _ in range(260):
+        p = int(rng.integers(2, 90)); m = int(rng.integers(2, 200)); qr = int(rng.integers(2, 24))
+        a, b, g = int(rng.integers(0, 50)), int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        q, sz, last = O.segmentation(m, qr)
+        if last == sz:
+            continue
+        seen += 1
         sizes = O.equi_sizes(m, qr)
         s = O.bi_greedy(p, sizes, a, b, g, mode=O.MODE_EVENT | O.MODE_PRUNE)
         c = [a + b * int(z) for z in sizes]; gg = [g * int(z) for z in sizes]
-        T, problems = validate("bi", p, c, gg, s.seg, s.src, s.dst, s.t, check_comm_comp=False)
-        assert not problems and T == s.T
+        T, problems = validate("bi", p, c, gg, s.seg, s.src, s.dst, s.t)
+        assert not problems and T == s.T, (p, list(sizes), a, b, g, problems[:3])
+        L = math.ceil(math.log2(p)); r = c[0] + gg[0]; rl = c[-1] + gg[-1]
+        assert (q - 1) * r + L * rl <= s.T <= (L + q - 2) * r + L * rl, (p, list(sizes), a, b, g, s.T)
+    assert seen >= 150
+
+
+def test_bi_section2_exclusion_matters_only_for_a_smaller_last_segment():
+    """The exclusion that keeps a combine out of a running send (Section 2) never fires with equal segments:
+    Algorithm 2 alone gives the same pairs.  With a smaller last segment Algorithm 2 alone overlaps a send
+    and a combine in many cases, the oracle in none."""
+    for p in (2, 3, 7, 16, 33):
+        for q in (1, 2, 5, 8):
+            for a, b, g in COSTS:
+                s = O.bi_greedy(p, [3] * q, a, b, g, mode=O.MODE_EVENT)
+                w = O.bi_greedy(p, [3] * q, a, b, g, mode=O.MODE_EVENT | O.MODE_LISTING_ONLY)
+                for f in ("src", "dst", "seg", "t"):
+                    assert np.array_equal(getattr(s, f), getattr(w, f))
+    rng = np.random.default_rng(8)
+    overlapping = 0
+    for _ in range(120):
+        p = int(rng.integers(3, 40)); q = int(rng.integers(2, 9)); sz = int(rng.integers(2, 9)); last = int(rng.integers(1, sz))
+        a, b, g = int(rng.integers(0, 20)), int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        sizes = [sz] * (q - 1) + [last]
+        c = [a + b * z for z in sizes]; gg = [g * z for z in sizes]
+        w = O.bi_greedy(p, sizes, a, b, g, mode=O.MODE_EVENT | O.MODE_LISTING_ONLY)
+        _, problems = validate("bi", p, c, gg, w.seg, w.src, w.dst, w.t)
+        assert all("communication overlaps computation" in x for x in problems)
+        overlapping += bool(problems)
+        s = O.bi_greedy(p, sizes, a, b, g, mode=O.MODE_EVENT)
+        assert not validate("bi", p, c, gg, s.seg, s.src, s.dst, s.t)[1]
+    assert overlapping >= 30
+
+
+def test_bi_fp64_schedules_are_valid_whatever_the_rounding():
+    """Seconds instead of integer units: event times that are equal on paper can differ in the last bit.  The
+    comparisons of Algorithm 2 between two transfers of the same segment size are decided by their start
+    times, so every schedule still passes the validator (equal and smaller last segment alike)."""
+    cfg = prs_inputs.uni_sweep(5000)
+    seen = ragged = 0
+    for i in range(0, 5000):
+        p, m, qr = int(cfg.p[i]), int(cfg.m[i]), int(cfg.q_req[i])
+        q, sz, last = O.segmentation(m, qr)
+        if (p - 1) * q > 2500 or q < 2:
+            continue
+        a, b, g = float(cfg.alpha[i]), float(cfg.beta[i]), float(cfg.gamma[i])
+        sizes = O.equi_sizes(m, qr)
+        s = O.bi_greedy(p, sizes, a, b, g, "f64", mode=O.MODE_EVENT | O.MODE_PRUNE)
+        c = [a + b * float(z) for z in sizes]; gg = [g * float(z) for z in sizes]
+        T, problems = validate("bi", p, c, gg, s.seg, s.src, s.dst, s.t)
+        assert s.status == 0 and not problems and T == s.T, (i, p, q, sz, last, problems[:2])
+        seen += 1; ragged += last != sz
+    assert seen >= 1500 and ragged >= 800
 
 
 def test_bi_fp64_equals_round_count_when_segments_are_equal():
