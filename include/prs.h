@@ -51,7 +51,9 @@ typedef enum { PRS_I32 = 0, PRS_F32 = 1, PRS_F64 = 2, PRS_I64 = 3 } prs_dtype;
 typedef enum { PRS_OP_SUM = 0, PRS_OP_MAX = 0x100 } prs_op;
 typedef enum {
     PRS_CFG_OK = 0,
-    PRS_CFG_BAD_PARAM = 1,   /* p < 2, q_req < 1, m < 1, a negative or non-finite cost, or tcomm = 0 */
+    PRS_CFG_BAD_PARAM = 1,   /* p < 2, q_req < 1, m < 1, a negative or non-finite cost, tcomm = 0, or a schedule too long for
+                                the cost type: (p-1+2(q-1))(alpha+beta s+gamma s), Table I's pipeline time which no greedy
+                                time passes, must stay below 4e18 (int64_t) or 1e300 (double) */
     PRS_CFG_TOO_LARGE = 2,   /* p > p_max, q_req > q_max, or the schedule does not fit pair_capacity */
     PRS_CFG_STALLED = 3      /* time could not advance (a cost vanished against the clock in rounding) */
 } prs_cfg_status;
@@ -88,6 +90,22 @@ typedef struct prs_times {
     int32_t *cfg_status; /* prs_cfg_status */
 } prs_times;
 
+/* Optional launch tuning of the sweep calls; NULL means the built-in choices.  It changes how
+ * configurations are spread over the lanes of a wavefront, never a result; tests use it to push one batch
+ * through every code path.
+ * uni_group_pairs[k]: a uni-greedy configuration of at most this many send/receive pairs is run by 1 (k=0),
+ *   4 (k=1) or 16 (k=2) lanes, larger ones by 32.  Used if the three are >= 0 and non-decreasing (all zero:
+ *   everything on 32 lanes -- also what a zeroed struct selects); otherwise, e.g. with -1, the built-in limits.
+ * uni_wave_log2: configurations of at least 2^uni_wave_log2 pairs get a whole wavefront (1..39; else built-in).
+ * bi_list_entries: most entries of the per-configuration list of running transfers in the bi-greedy kernel
+ *   for p <= 1024; a configuration that needs more is rerun by the general kernel (1 .. built-in size; else
+ *   built-in). */
+typedef struct prs_tuning {
+    int64_t uni_group_pairs[3];
+    int32_t uni_wave_log2;
+    int32_t bi_list_entries;
+} prs_tuning;
+
 /* Bytes of device scratch the given call needs for a batch of n
  * configurations with p <= p_max and q_req <= q_max (for PRS_CALL_REPLAY:
  * n = 1, p_max = p, q_max = q; for PRS_CALL_UNEQUAL: q_max = m_max).  Host
@@ -100,7 +118,11 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
  * 4, 5.2, 6.1).  model = PRS_UNI runs Algorithm 1 (Section 5): per segment,
  * p-1 times, the two processors with the smallest ready times pair up at the
  * larger of the two.  model = PRS_BI runs Algorithm 2 (Section 6.2), its unit
- * time step replaced by a jump to the next time a port frees.
+ * time step replaced by a jump to the next time at which a pair can form (a
+ * port frees, or a processor may take in the smaller last segment: Section 2
+ * lets no combine start while the processor still sends, so with a smaller
+ * last segment it receives that segment only from the end of its running
+ * send minus tcomm(last) on).
  * cfg, out: host structs holding device pointers.  p_max, q_max: upper bounds
  * on p and q_req in the batch (they size the workspace).
  * Errors: PRS_EINVAL for a NULL struct/array, n < 0, bad enum or bounds;
@@ -108,7 +130,7 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
  */
 int simulate_completion_batch(const prs_configs *cfg, int64_t n, int model, int cost,
                               int32_t p_max, int32_t q_max, const prs_times *out,
-                              void *workspace, size_t workspace_bytes, void *stream);
+                              void *workspace, size_t workspace_bytes, void *stream, const prs_tuning *tuning);
 
 /*
  * pair_offset[i] = sum over j < i of (p_j - 1) * q_eff_j, for i = 0..n
@@ -135,7 +157,7 @@ int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost
                           const int64_t *pair_offset, int64_t pair_capacity,
                           int32_t *src, int32_t *dst, int32_t *seg, void *t_start,
                           void *T_greedy, int32_t *cfg_status,
-                          void *workspace, size_t workspace_bytes, void *stream);
+                          void *workspace, size_t workspace_bytes, void *stream, const prs_tuning *tuning);
 
 /*
  * Executes one schedule on data (Section 4: the receiver of a pair combines
@@ -187,7 +209,7 @@ typedef struct prs_best {
  */
 int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int cost,
                                int32_t p_max, int32_t q_max, const prs_best *out,
-                               void *workspace, size_t workspace_bytes, void *stream);
+                               void *workspace, size_t workspace_bytes, void *stream, const prs_tuning *tuning);
 
 /* Result columns of unequal_segmentation_batch, DEVICE pointers, any of them
  * may be NULL.  T_* have the cost type of the call. */
@@ -220,7 +242,8 @@ typedef struct prs_unequal {
  * prs_workspace_bytes(PRS_CALL_UNEQUAL, PRS_UNI, cost, n, p_max, m_max).
  */
 int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t m_max,
-                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream);
+                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream,
+                               const prs_tuning *tuning);
 
 /* Version of the ABI, bumped on any incompatible change. */
 int prs_abi_version(void);

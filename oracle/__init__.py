@@ -111,6 +111,19 @@ def uni_greedy(p, sizes, alpha, beta, gamma, cost="i64", want_schedule=True) -> 
     return Schedule(src, dst, seg, t, T.value, 0, xf)
 
 
+def uni_greedy_time(p, sizes, alpha, beta, gamma, cost="i64"):
+    """Completion time of uni-greedy from the ready times alone (a heap of values, no processor identities):
+    for machines of tens of thousands of processors."""
+    _, ct, suf = _ct(cost)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    T = ct()
+    rc = getattr(lib(), "orc_uni_greedy_values" + suf)(C.c_int32(p), C.c_int32(int(sizes.shape[0])), _ptr(sizes, C.c_int64),
+                                                       ct(alpha), ct(beta), ct(gamma), C.byref(T))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return T.value
+
+
 def bi_greedy(p, sizes, alpha, beta, gamma, cost="i64", mode=MODE_EVENT, want_schedule=True) -> Schedule:
     npt, ct, suf = _ct(cost)
     sizes = np.ascontiguousarray(sizes, dtype=np.int64)

@@ -49,6 +49,22 @@ class _Unequal(C.Structure):
                                           "equi_optimal", "cfg_status")]
 
 
+class _Tuning(C.Structure):
+    _fields_ = [("uni_group_pairs", C.c_int64 * 3), ("uni_wave_log2", C.c_int32), ("bi_list_entries", C.c_int32)]
+
+
+def _tuning(t):
+    """None, or a dict with any of uni_group_pairs (three limits), uni_wave_log2, bi_list_entries -> prs_tuning*."""
+    if t is None:
+        return None
+    unknown = set(t) - {"uni_group_pairs", "uni_wave_log2", "bi_list_entries"}
+    if unknown:
+        raise PrsError(f"unknown tuning fields {sorted(unknown)}")
+    pairs = t.get("uni_group_pairs", (-1, -1, -1))
+    return C.byref(_Tuning((C.c_int64 * 3)(*[int(v) for v in pairs]), int(t.get("uni_wave_log2", 0)),
+                           int(t.get("bi_list_entries", 0))))
+
+
 def library_path() -> str:
     return os.path.join(_HERE, "libprs.so")
 
@@ -67,24 +83,24 @@ def load_library():
         lib.prs_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int32, C.c_int32]
         lib.simulate_completion_batch.restype = C.c_int
         lib.simulate_completion_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
-                                                  C.POINTER(_Times), C.c_void_p, C.c_size_t, C.c_void_p]
+                                                  C.POINTER(_Times), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.prs_pair_offsets.restype = C.c_int
         lib.prs_pair_offsets.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int32, C.c_int32, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.greedy_schedule_batch.restype = C.c_int
         lib.greedy_schedule_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
                                               C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.replay_reduction.restype = C.c_int
         lib.replay_reduction.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                          C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.optimal_segmentation_batch.restype = C.c_int
         lib.optimal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
-                                                   C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p]
+                                                   C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.unequal_segmentation_batch.restype = C.c_int
         lib.unequal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int32, C.c_int32,
-                                                   C.POINTER(_Unequal), C.c_void_p, C.c_size_t, C.c_void_p]
+                                                   C.POINTER(_Unequal), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         _LIB = lib
     return _LIB
 
@@ -151,7 +167,7 @@ def _aligned_ptr(ws):
 
 
 def simulate_completion_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int, out: dict | None = None,
-                              workspace=None):
+                              workspace=None, tuning=None):
     """Returns a dict of device tensors: greedy, binomial, pipeline, binary, revopt (cost type), butterfly,
     lower_bound (float64), q_eff, cfg_status (int32).  `out` may pre-allocate any of them (None = skip)."""
     import torch
@@ -168,13 +184,14 @@ def simulate_completion_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max:
     times = _Times(*[(out.get(k).data_ptr() if out.get(k) is not None else None) for k, _ in _Times._fields_])
     cs = cfg.struct()
     rc = lib.simulate_completion_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, C.byref(times),
-                                       C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+                                       C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream(),
+                                       _tuning(tuning))
     _check(rc, "simulate_completion_batch")
     out["_workspace"] = ws
     return out
 
 
-def optimal_segmentation_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int, workspace=None):
+def optimal_segmentation_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int, workspace=None, tuning=None):
     """Best power-of-two segment count per algorithm.  Returns a dict of device tensors: T_greedy, T_pipeline,
     T_binary, T_revopt (cost type), q_greedy, q_pipeline, q_binary, q_revopt, cfg_status (int32).  cfg.q_req is
     not read."""
@@ -191,13 +208,14 @@ def optimal_segmentation_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max
     best = _Best(*[out[k].data_ptr() for k, _ in _Best._fields_])
     cs = cfg.struct()
     rc = lib.optimal_segmentation_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, C.byref(best),
-                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream(),
+                                        _tuning(tuning))
     _check(rc, "optimal_segmentation_batch")
     out["_workspace"] = ws
     return out
 
 
-def unequal_segmentation_batch(cfg: DeviceConfigs, p_max: int, m_max: int, want_all=True, workspace=None):
+def unequal_segmentation_batch(cfg: DeviceConfigs, p_max: int, m_max: int, want_all=True, workspace=None, tuning=None):
     """Every segmentation of cfg.m <= m_max units through uni-greedy.  Returns a dict of device tensors: T_all
     (n x 2^(m_max-1), cost type, only if want_all), T_best, T_equi (cost type), cuts_best, cuts_equi (int32 holding
     the cut patterns), n_best, equi_optimal, cfg_status (int32).  cfg.q_req is not read."""
@@ -215,7 +233,8 @@ def unequal_segmentation_batch(cfg: DeviceConfigs, p_max: int, m_max: int, want_
     res = _Unequal(*[None if out[k] is None else out[k].data_ptr() for k, _ in _Unequal._fields_])
     cs = cfg.struct()
     rc = lib.unequal_segmentation_batch(C.byref(cs), n, cfg.cost, p_max, m_max, C.byref(res),
-                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+                                        C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream(),
+                                        _tuning(tuning))
     _check(rc, "unequal_segmentation_batch")
     out["_workspace"] = ws
     return out
@@ -234,7 +253,7 @@ def prs_pair_offsets(cfg: DeviceConfigs, p_max: int, q_max: int):
 
 def greedy_schedule_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int, pair_offset, pair_capacity: int,
                           src=None, dst=None, seg=None, t_start=None, want=("src", "dst", "seg", "t_start"),
-                          workspace=None):
+                          workspace=None, tuning=None):
     """Returns dict(src, dst, seg, t_start, T_greedy, cfg_status) of device tensors."""
     import torch
     lib = load_library()
@@ -253,7 +272,8 @@ def greedy_schedule_batch(cfg: DeviceConfigs, model: int, p_max: int, q_max: int
     cs = cfg.struct()
     rc = lib.greedy_schedule_batch(C.byref(cs), n, model, cfg.cost, p_max, q_max, _dp(pair_offset), cap,
                                    _dp(src), _dp(dst), _dp(seg), _dp(t_start), _dp(T), _dp(st),
-                                   C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
+                                   C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream(),
+                                   _tuning(tuning))
     _check(rc, "greedy_schedule_batch")
     return {"src": src, "dst": dst, "seg": seg, "t_start": t_start, "T_greedy": T, "cfg_status": st, "_workspace": ws}
 

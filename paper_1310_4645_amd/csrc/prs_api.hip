@@ -1,8 +1,5 @@
 // C ABI of the library (declared in include/prs.h): argument checks, workspace
 // carving and kernel launches.  No device memory is allocated here.
-#include <stdio.h>
-#include <stdlib.h>
-
 #include "prs_device.h"
 #include "prs_launch.h"
 
@@ -100,7 +97,7 @@ struct Layout {
 
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
-static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t q_max)
+static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t q_max, const prs_tuning *tuning = nullptr)
 {
     Layout L;
     const bool sched = call == PRS_CALL_SCHEDULE;
@@ -121,15 +118,10 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         // described by class 0
         L.limits.by_work = 1;
         for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kUniWork[k];
-        // tuning and test knob: "a,b,c" replaces the three limits (0,0,0 sends everything to the largest groups)
-        // (a fourth value replaces the binary logarithm of the pair count from which a configuration gets a whole wavefront)
-        if (const char *env = getenv("PRS_UNI_GROUP_WORK")) {
-            long long a = 0, b = 0, c3 = 0, g = kGiantLog2;
-            const int got = sscanf(env, "%lld,%lld,%lld,%lld", &a, &b, &c3, &g);
-            if (got >= 3 && a >= 0 && b >= a && c3 >= b) {
-                L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3;
-                if (got == 4 && g >= 0 && g < kWorkBuckets) L.limits.giant_log2 = static_cast<int32_t>(g);
-            }
+        if (tuning) {                                              // never changes a result, only who runs what
+            const int64_t a = tuning->uni_group_pairs[0], b = tuning->uni_group_pairs[1], c3 = tuning->uni_group_pairs[2];
+            if (a >= 0 && b >= a && c3 >= b) { L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3; }
+            if (tuning->uni_wave_log2 > 0 && tuning->uni_wave_log2 < kWorkBuckets) L.limits.giant_log2 = tuning->uni_wave_log2;
         }
         for (int k = 0; k < kClasses; ++k) {
             ClassSpec &c = L.cls[k];
@@ -218,12 +210,12 @@ static bool bad_common(const prs_configs *cfg, int64_t n, int model, int cost, i
 
 static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
                       const TimesOut &times, const SchedOut &sched, void *workspace, size_t workspace_bytes, void *stream,
-                      int32_t comp_m = 0)
+                      const prs_tuning *tuning, int32_t comp_m = 0)
 {
     if (comp_m > 0 && (call != PRS_CALL_SIMULATE || model != PRS_UNI)) return PRS_EINVAL;   // compositions: uni-greedy times only
     if (n == 0) return PRS_OK;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PRS_EINVAL;
-    const Layout lay = make_layout(call, model, n, p_max, q_max);
+    const Layout lay = make_layout(call, model, n, p_max, q_max, tuning);
     if (workspace_bytes < lay.total) return PRS_ENOSPC;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -278,6 +270,8 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             for (int g = 0; g < 3; ++g) {
                 G.parts.on[g] = lay.cls[g].kind == kBiGroup && lay.cls[g].lpc > 0 && lay.cls[g].rows_per_group > 0 && lay.bi_on[g];
                 G.parts.rows_per_group[g] = lay.cls[g].rows_per_group;
+                const int cap = bi_group_list_capacity(g == 0 ? 1 : (g == 1 ? 4 : 16));
+                G.parts.list_entries[g] = (tuning && tuning->bi_list_entries > 0 && tuning->bi_list_entries < cap) ? tuning->bi_list_entries : cap;
                 if (G.parts.on[g]) enabled += share[g];
             }
             int given = 0;
@@ -496,7 +490,7 @@ using namespace prs;
 
 extern "C" {
 
-int prs_abi_version(void) { return 1; }
+int prs_abi_version(void) { return 2; }
 
 size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_max, int32_t q_max)
 {
@@ -514,17 +508,19 @@ size_t prs_workspace_bytes(int call, int model, int cost, int64_t n, int32_t p_m
 }
 
 int simulate_completion_batch(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
-                              const prs_times *out, void *workspace, size_t workspace_bytes, void *stream)
+                              const prs_times *out, void *workspace, size_t workspace_bytes, void *stream,
+                              const prs_tuning *tuning)
 {
     if (bad_common(cfg, n, model, cost, p_max, q_max) || !out) return PRS_EINVAL;
     TimesOut t{out->greedy, out->binomial, out->pipeline, out->binary, out->revopt,
                out->butterfly, out->lower_bound, out->q_eff, out->cfg_status};
     SchedOut s{};
-    return run_greedy(PRS_CALL_SIMULATE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream);
+    return run_greedy(PRS_CALL_SIMULATE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream, tuning);
 }
 
 int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
-                               const prs_best *out, void *workspace, size_t workspace_bytes, void *stream)
+                               const prs_best *out, void *workspace, size_t workspace_bytes, void *stream,
+                               const prs_tuning *tuning)
 {
     if (!cfg || !out || n < 0 || n >= (INT64_C(1) << 26) || (model != PRS_UNI && model != PRS_BI) ||
         (cost != PRS_COST_I64 && cost != PRS_COST_F64) || p_max < 2 || p_max > (1 << 20) || q_max < 1 || q_max > (1 << 20))
@@ -555,7 +551,7 @@ int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int
                reinterpret_cast<int32_t *>(ws + S.status)};
     SchedOut s{};
     const int rc = run_greedy(PRS_CALL_SIMULATE, &exp_cfg, n_exp, model, cost, p_max, q_max, t, s, ws + S.sim,
-                              workspace_bytes - S.sim, stream);
+                              workspace_bytes - S.sim, stream, tuning);
     if (rc != PRS_OK) return rc;
     BestOut b{{out->T_greedy, out->T_pipeline, out->T_binary, out->T_revopt},
               {out->q_greedy, out->q_pipeline, out->q_binary, out->q_revopt}, out->cfg_status};
@@ -574,7 +570,8 @@ int optimal_segmentation_batch(const prs_configs *cfg, int64_t n, int model, int
 }
 
 int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t m_max,
-                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream)
+                               const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream,
+                               const prs_tuning *tuning)
 {
     if (!cfg || !out || n < 0 || (cost != PRS_COST_I64 && cost != PRS_COST_F64) || p_max < 2 || p_max > (1 << 20) ||
         m_max < 1 || m_max > kUnequalMaxM || (n << (m_max - 1)) >= (INT64_C(1) << 31))
@@ -591,7 +588,7 @@ int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int3
     TimesOut t{all, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, status};
     SchedOut s{};
     const int rc = run_greedy(PRS_CALL_SIMULATE, &problems, U.n_exp, PRS_UNI, cost, p_max, m_max, t, s, ws + U.sim,
-                              workspace_bytes - U.sim, stream, m_max);
+                              workspace_bytes - U.sim, stream, tuning, m_max);
     if (rc != PRS_OK) return rc;
     const ConfigArrays in{cfg->p, nullptr, cfg->m, cfg->alpha, cfg->beta, cfg->gamma};
     const UnequalOut u{out->T_best, out->cuts_best, out->n_best, out->T_equi, out->cuts_equi, out->equi_optimal, out->cfg_status};
@@ -618,12 +615,12 @@ int prs_pair_offsets(const prs_configs *cfg, int64_t n, int cost, int32_t p_max,
 int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost, int32_t p_max, int32_t q_max,
                           const int64_t *pair_offset, int64_t pair_capacity, int32_t *src, int32_t *dst, int32_t *seg,
                           void *t_start, void *T_greedy, int32_t *cfg_status, void *workspace, size_t workspace_bytes,
-                          void *stream)
+                          void *stream, const prs_tuning *tuning)
 {
     if (bad_common(cfg, n, model, cost, p_max, q_max) || pair_capacity < 0 || (n > 0 && !pair_offset)) return PRS_EINVAL;
     TimesOut t{};
     SchedOut s{pair_offset, pair_capacity, src, dst, seg, t_start, T_greedy, cfg_status};
-    return run_greedy(PRS_CALL_SCHEDULE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream);
+    return run_greedy(PRS_CALL_SCHEDULE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream, tuning);
 }
 
 int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset, const int32_t *src, const int32_t *dst,

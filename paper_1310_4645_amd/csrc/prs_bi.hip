@@ -39,7 +39,7 @@ __host__ __device__ inline BiSmall bi_small_layout(int32_t p_cap, int32_t q_cap)
     const size_t p = static_cast<size_t>(p_cap), q = static_cast<size_t>(q_cap);
     L.W = static_cast<int>((p + 63) / 64);
     size_t o = 0;
-    L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 6);   // 6 word arrays
+    L.masks = o; o += bi_align(static_cast<size_t>(L.W) * 8 * 7);   // 7 word arrays
     L.pref = o; o += bi_align(static_cast<size_t>(L.W) * 4 * 2);
     L.sendList = o; o += bi_align((p / 2 + 1) * 4);
     L.recvList = o; o += bi_align((p / 2 + 1) * 4);
@@ -103,6 +103,11 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
     const int Wc = bs.Wcap;
     uint64_t *sfree = mk, *rfree = mk + Wc, *compF = mk + 2 * Wc, *compL = mk + 3 * Wc;
     uint64_t *sendSet = mk + 4 * Wc, *recvSet = mk + 5 * Wc;
+    uint64_t *lateL = mk + 6 * Wc;                      // senders whose send outlasts a transfer of the smaller last segment begun now
+    // nsent[i] also carries the kind of i's latest transfers: bit 30 = it last sent the smaller last segment,
+    // bit 29 = it last received it
+    constexpr int32_t kSentShort = 1 << 30, kRecvShort = 1 << 29, kCount = kRecvShort - 1;
+    const bool ragged = c.sz_last != c.sz, guardL = ragged && c.g_last > 0;
     int32_t *prefS = reinterpret_cast<int32_t *>(mbase + bs.sl.pref), *prefR = prefS + Wc;
     int32_t *sendList = reinterpret_cast<int32_t *>(bs.small + bs.sl.sendList);
     int32_t *recvList = reinterpret_cast<int32_t *>(bs.small + bs.sl.recvList);
@@ -133,7 +138,7 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                 const int i = (w4 + u) * kWave + lane;
                 const bool in = i < p;
                 s4[u] = in ? S[i] : 0; r4[u] = in ? R[i] : 0; c4[u] = in ? C1[i] : 0;
-                n4[u] = in ? nsent[i] : q;
+                n4[u] = in ? nsent[i] : 0;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -142,17 +147,25 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                 const bool in = i < p;
                 const T s = s4[u], r = r4[u], c1 = c4[u];
                 const int32_t nsnt = n4[u];
-                const bool live = in && (i == 0 || nsnt < q);          // still a member of some segment
+                const bool live = in && (i == 0 || (nsnt & kCount) < q);   // still a member of some segment
                 const bool sf = live && i != 0 && s <= t;              // the root never sends
                 const bool rf = live && r <= t;
                 const bool busy = in && c1 <= t && t < r;              // computing now
                 const bool pend = in && t < c1;                        // computation scheduled ahead
-                const bool cF = busy || (pend && t + c.c_full > c1);
-                const bool cL = busy || (pend && t + c.c_last > c1);
+                // A transfer begun now must not run into that computation.  It was scheduled before t: against a
+                // segment of its own size that settles it (comparing the two rounded sums could miss it by one
+                // rounding error); against the other size the sums are compared.
+                const bool rshort = (nsnt & kRecvShort) != 0;
+                const bool cF = busy || (pend && (!rshort || t + c.c_full > c1));
+                const bool cL = busy || (pend && (rshort || !ragged || t + c.c_last > c1));
+                // Section 2 the other way round: the combine of the smaller last segment, received now, would begin
+                // while this processor is still sending a full one; it becomes eligible at s - tcomm(last)
+                const bool lt = in && guardL && !(nsnt & kSentShort) && s > t + c.c_last;
                 if (in && s > t && s < minOld) minOld = s;
                 if (in && r > t && r < minOld) minOld = r;
-                const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL);
-                if (lane == 0 && w < W) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; }
+                if (lt) { const T v = s - c.c_last; if (v > t && v < minOld) minOld = v; }
+                const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL), blt = ballot64(lt);
+                if (lane == 0 && w < W) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; lateL[w] = blt; }
                 cs += __popcll(bsf & ~bcL);
                 cr += __popcll(brf & ~bcL);
                 cu += __popcll((bsf | brf) & ~bcL);
@@ -180,7 +193,7 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                     if (w == W - 1 && (p & 63)) valid = (UINT64_C(1) << (p & 63)) - 1;
                     const uint64_t memb = ~sent[static_cast<size_t>(j) * W + w] & valid;
                     const uint64_t comp = last ? compL[w] : compF[w];
-                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w];
+                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w] & ~(last ? lateL[w] : UINT64_C(0));
                     const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
                     ns_ += __popcll(so); nr_ += __popcll(ro); nf_ += __popcll(fr);
                 }
@@ -211,7 +224,7 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                     if (w == W - 1 && (p & 63)) valid = (UINT64_C(1) << (p & 63)) - 1;
                     const uint64_t memb = ~sent[static_cast<size_t>(j) * W + w] & valid;
                     const uint64_t comp = last ? compL[w] : compF[w];
-                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w];
+                    const uint64_t sOK = memb & ~comp & sfree[w], rOK = memb & ~comp & rfree[w] & ~(last ? lateL[w] : UINT64_C(0));
                     fr = sOK & rOK; so = sOK ^ fr; ro = rOK ^ fr;
                 }
                 const int pf = __popcll(fr);
@@ -256,10 +269,12 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             // ---- pass D: entry-wise pairing
             const T tc = t + cj, tr = tc + gj;
             if (!(tc > t)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
+            const bool shortNow = last && ragged;
             for (int e = lane; e < l; e += kWave) {
-                const int32_t a = sendList[e], b = recvList[e];
+                const int32_t a = sendList[e], b = recvList[e];        // no processor is in both lists of a visit
                 S[a] = tc;
-                nsent[a] += 1;
+                nsent[a] = (((nsent[a] & kCount) + 1) | (nsent[a] & kRecvShort)) | (shortNow ? kSentShort : 0);
+                nsent[b] = (nsent[b] & ~kRecvShort) | (shortNow ? kRecvShort : 0);
                 R[b] = tr;
                 C1[b] = tc;
                 if (kSched) {
@@ -273,6 +288,12 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             emitted += l;
             if (tc < minNew) minNew = tc;
             if (tr < minNew) minNew = tr;
+            if (guardL && !last && tc > t + c.c_last) {           // these senders cannot take the last segment in yet
+                for (int w0 = 0; w0 < W; w0 += kWave)
+                    if (w0 + lane < W) lateL[w0 + lane] |= sendSet[w0 + lane];
+                const T v = tc - c.c_last;
+                if (v > t && v < minNew) minNew = v;
+            }
             cs -= l; cr -= l;
             cu -= wave_sum(gone);
             remj -= l;

@@ -24,12 +24,9 @@ namespace prs {
 constexpr int kPlanes = 10;            // bit planes of the sent-segments counter: q <= 1023
 
 // Entries of the list of running groups per configuration.  A configuration that needs more is handed
-// to the one-configuration kernel.  PRS_BI_GROUP_CAP shrinks the list in test builds to force that path.
-#ifdef PRS_BI_GROUP_CAP
-__host__ __device__ constexpr int bi_group_capacity(int) { return PRS_BI_GROUP_CAP; }
-#else
+// to the one-configuration kernel; a launch may lower the limit (never the LDS layout) to force that path.
 __host__ __device__ constexpr int bi_group_capacity(int lpc) { return lpc == 1 ? 16 : (lpc == 4 ? 22 : 28); }
-#endif
+int bi_group_list_capacity(int lpc) { return bi_group_capacity(lpc); }
 
 // LDS per wavefront: `cap` list entries, each with the two set words of every lane and the two times of
 // every configuration in the wavefront
@@ -132,7 +129,7 @@ template <typename T, bool kSched, int LPC>
 __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const ConfigArrays &cfg, int32_t p_max, int32_t q_max,
                                               int model, const TimesOut &times, const SchedOut &sched, PlanHeader *plan,
                                               const int32_t *order, int cls, int32_t *retry, uint64_t *rows,
-                                              size_t rows_per_group)
+                                              size_t rows_per_group, int list_entries)
 {
     constexpr int kCap = bi_group_capacity(LPC);
     const int lane = lane_id();
@@ -165,6 +162,9 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     bool need_event = true, overflow = false, idle_visit = false;
     int64_t emitted = 0, out_base = 0, events = 0;
     uint64_t valid = 0, sfree = 0, rfree = 0, compF = 0, compL = 0;   // this lane's word
+    uint64_t lateL = 0;         // this lane's word: senders whose send outlasts a transfer of the smaller last segment begun now
+    uint32_t shortMask = 0;     // bit s: list entry s carries the smaller last segment
+    bool ragged = false, guardL = false;   // the last segment is smaller; and its combine takes time
     uint64_t cnt[kPlanes];      // bit-sliced: segments sent per processor
     uint64_t nxt_seg[kPlanes];  // bit-sliced: a segment index below which the processor has sent everything
 #pragma unroll
@@ -194,6 +194,9 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 valid = 0;
                 if (gl < W) valid = (gl == W - 1 && (c.p & 63)) ? (UINT64_C(1) << (c.p & 63)) - 1 : ~UINT64_C(0);
                 t = 0; Tmax = 0; minNew = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
+                shortMask = 0; lateL = 0;
+                ragged = c.sz_last != c.sz;
+                guardL = ragged && c.g_last > 0;
                 need_event = true; overflow = false; idle_visit = false; emitted = 0; events = 0;
 #pragma unroll
                 for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
@@ -230,6 +233,11 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
                     if (se > t && se < tn) tn = se;
                     if (re > t && re < tn) tn = re;
+                    // senders of a full segment may receive the smaller last one from se - tcomm(last) on
+                    if (guardL && !((shortMask >> s) & 1) && se > t + c.c_last) {
+                        const T v = se - c.c_last;
+                        if (v > t && v < tn) tn = v;
+                    }
                 }
                 if (!(tn < kInf)) status = PRS_CFG_STALLED;
             }
@@ -237,7 +245,8 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             t = tn;
             minNew = kInf;
             // rebuild the port and computation sets from the groups still running; drop finished groups
-            uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0;
+            uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0, late = 0;
+            uint32_t keptShort = 0;
             int keep = 0;
             const int nxt = kBufs == 1 ? 0 : cur ^ 1;
 #pragma unroll 4
@@ -249,15 +258,25 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     if (re > t) rbusy |= rm;
                     const bool busy = se <= t && t < re;                  // receivers are computing
                     const bool pend = t < se;                             // their computation starts at se
-                    if (busy || (pend && t + c.c_full > se)) cF |= rm;
-                    if (busy || (pend && t + c.c_last > se)) cL |= rm;
+                    // A transfer begun now must not run into that computation.  The entry began before t: against
+                    // a segment of its own size that settles it (comparing the two rounded sums could miss it by
+                    // one rounding error); against the other size the sums are compared.
+                    const bool shortEntry = (shortMask >> s) & 1;
+                    if (busy || (pend && (!shortEntry || t + c.c_full > se))) cF |= rm;
+                    if (busy || (pend && (shortEntry || !ragged || t + c.c_last > se))) cL |= rm;
+                    // Section 2 the other way round: the combine of the smaller last segment, received now, would
+                    // begin while the sender of a full segment is still sending
+                    if (guardL && !shortEntry && se > t + c.c_last) late |= sm;
                     gS[(nxt * kCap + keep) * kGroups + gw] = se;          // same value from every lane of the group
                     gR[(nxt * kCap + keep) * kGroups + gw] = re;
                     if (keep != s) { gSm[keep * kWave + lane] = sm; gRm[keep * kWave + lane] = rm; }
+                    if (shortEntry) keptShort |= 1u << keep;
                     ++keep;
                 }
             }
             ng = keep;
+            shortMask = keptShort;
+            lateL = late;
             cur = nxt;
             // processors that have sent all q segments take part in nothing any more
             uint64_t fin = ~UINT64_C(0);
@@ -302,7 +321,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     if (pairable && cand < c.q - 1) jn = cand;
                 }
                 if (jn == kNoSegment && j <= c.q - 1) {               // only the last segment is left to try
-                    const uint64_t as = sfree & ~compL, ar = rfree & ~compL;
+                    const uint64_t as = sfree & ~compL, ar = rfree & ~compL & ~lateL;
                     int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
                     ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
                     nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
@@ -327,7 +346,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     ++j;
                 } else {
                     const uint64_t comp = last ? compL : compF;
-                    const uint64_t sOK = memb & ~comp & sfree, rOK = memb & ~comp & rfree;
+                    const uint64_t sOK = memb & ~comp & sfree, rOK = memb & ~comp & rfree & ~(last ? lateL : UINT64_C(0));
                     const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
                     const int pf = __popcll(fr);
                     const int ns_ = group_sum<LPC>(__popcll(so)), nr_ = group_sum<LPC>(__popcll(ro)), nf_ = group_sum<LPC>(pf);
@@ -386,15 +405,21 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         rfree &= ~rset;
                         sliced_increment(cnt, sset);                     // one more sent segment for the senders
                         sliced_increment(nxt_seg, sliced_equal(nxt_seg, sset, j));
-                        if (ng < kCap) {
+                        if (ng < list_entries) {
                             gS[(cur * kCap + ng) * kGroups + gw] = tc; gR[(cur * kCap + ng) * kGroups + gw] = tr;
                             gSm[ng * kWave + lane] = sset; gRm[ng * kWave + lane] = rset;
+                            if (last && ragged) shortMask |= 1u << ng;
                             ++ng;
                         } else {
                             overflow = true;
                         }
                         if (tc < minNew) minNew = tc;
                         if (tr < minNew) minNew = tr;
+                        if (guardL && !last && tc > t + c.c_last) {      // these senders cannot take the last segment in yet
+                            lateL |= sset;
+                            const T v = tc - c.c_last;
+                            if (v > t && v < minNew) minNew = v;
+                        }
                         remj -= l;
                         if (remj == 0) {                                  // only the root is left: done after the last arrival
                             if (tr > Tmax) Tmax = tr;
@@ -440,13 +465,13 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
         if (!parts.on[cls]) continue;
         if (cls == 2)
             bi_group_body<T, kSched, 16>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, rows,
-                                         parts.rows_per_group[2]);
+                                         parts.rows_per_group[2], parts.list_entries[2]);
         else if (cls == 1)
             bi_group_body<T, kSched, 4>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 1, retry, rows,
-                                        parts.rows_per_group[1]);
+                                        parts.rows_per_group[1], parts.list_entries[1]);
         else
             bi_group_body<T, kSched, 1>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 0, retry, rows,
-                                        parts.rows_per_group[0]);
+                                        parts.rows_per_group[0], parts.list_entries[0]);
         __syncthreads();
     }
 }

@@ -22,12 +22,27 @@ template <> struct CostTraits<int64_t> {
     static __device__ __forceinline__ int64_t inf() { return INT64_MAX; }
     static __device__ __forceinline__ int64_t bad() { return -1; }
     static __device__ __forceinline__ bool valid(int64_t v) { return v >= 0 && v < (INT64_C(1) << 62); }
+    static __device__ __forceinline__ bool fits(double total) { return total < 4.0e18; }       // below 2^62
 };
 template <> struct CostTraits<double> {
     static __device__ __forceinline__ double inf() { return __builtin_huge_val(); }
     static __device__ __forceinline__ double bad() { return __builtin_nan(""); }
     static __device__ __forceinline__ bool valid(double v) { return v >= 0.0 && v < __builtin_huge_val(); }
+    static __device__ __forceinline__ bool fits(double total) { return total < 1.0e300; }
 };
+
+// No time of a greedy schedule passes the pipeline's (p-1 + 2(q-1)) rounds of the longest segment (Table I; Theorem 1
+// puts uni-greedy below every algorithm that takes the segments in order, and a round of the longest segment covers
+// any segment).  A configuration whose bound does not fit the cost type is refused: past it sums would overflow, and
+// the largest representable value doubles as "no entry" in the kernels.
+template <typename T>
+__device__ __forceinline__ bool schedule_fits(int32_t p, int64_t q, T alpha, T beta, T gamma, int64_t sz)
+{
+    const double round = (static_cast<double>(alpha) + static_cast<double>(beta) * static_cast<double>(sz)) +
+                         static_cast<double>(gamma) * static_cast<double>(sz);
+    const double rounds = static_cast<double>(p - 1) + 2.0 * static_cast<double>(q - 1);
+    return CostTraits<T>::fits(rounds * round);
+}
 
 // One configuration after decoding (Section 2: equi-segmentation; Section 5:
 // tcomm and tcomp of a segment).  Only two distinct segment sizes occur.
@@ -90,6 +105,7 @@ __device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_
         // the smallest and the largest cost a segment of this problem can have (sizes 1 and m)
         const T c1 = c.alpha + c.beta, cm = c.alpha + c.beta * static_cast<T>(c.m), gm = c.gamma * static_cast<T>(c.m);
         if (!(c1 > 0) || !(cm > 0) || !CostTraits<T>::valid(cm) || !CostTraits<T>::valid(gm)) c.status = PRS_CFG_BAD_PARAM;
+        if (!schedule_fits<T>(c.p, c.q, c.alpha, c.beta, c.gamma, c.m)) c.status = PRS_CFG_BAD_PARAM;
         return c;
     }
     c.p = a.p[i];
@@ -120,6 +136,7 @@ __device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_
     c.g_last = c.gamma * static_cast<T>(c.sz_last);
     if (!(c.c_full > 0) || !(c.c_last > 0) || !CostTraits<T>::valid(c.c_full) || !CostTraits<T>::valid(c.g_full))
         c.status = PRS_CFG_BAD_PARAM;
+    if (!schedule_fits<T>(c.p, q, c.alpha, c.beta, c.gamma, c.sz)) c.status = PRS_CFG_BAD_PARAM;
     return c;
 }
 

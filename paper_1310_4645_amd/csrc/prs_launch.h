@@ -58,6 +58,7 @@ struct BiGroupParts {
     uint64_t *rows;               // sent-bit rows: one slot of rows_per_block words per block
     size_t rows_per_block;
     size_t rows_per_group[3];
+    int list_entries[3];          // entries of the list of running transfers a configuration may use (<= the LDS layout's)
 };
 struct BiGroupLaunch {
     ConfigArrays cfg;
@@ -73,6 +74,7 @@ struct BiGroupLaunch {
     hipStream_t stream;
 };
 size_t bi_group_lds_bytes(int lpc);
+int bi_group_list_capacity(int lpc);
 hipError_t launch_bi_group(const BiGroupLaunch &L);
 // uni-greedy: all classes of a batch in one launch
 size_t uni_times_lds_bytes();

@@ -63,7 +63,7 @@ def _oracle_schedules(host, model):
     return out
 
 
-def _check_schedules(prs, host, model, p_max, q_max, exact_t=True):
+def _check_schedules(prs, host, model, p_max, q_max, exact_t=True, tuning=None):
     dev = prs.DeviceConfigs.from_host(host)
     off = prs.prs_pair_offsets(dev, p_max, q_max)
     _sync()
@@ -71,7 +71,7 @@ def _check_schedules(prs, host, model, p_max, q_max, exact_t=True):
     refs = _oracle_schedules(host, model)
     want_off = np.concatenate([[0], np.cumsum([len(r.src) for r in refs])])
     assert np.array_equal(offh, want_off)
-    sch = prs.greedy_schedule_batch(dev, model, p_max, q_max, off, int(offh[-1]))
+    sch = prs.greedy_schedule_batch(dev, model, p_max, q_max, off, int(offh[-1]), tuning=tuning)
     _sync()
     src, dst, seg, t, T = (_np(sch[k]) for k in ("src", "dst", "seg", "t_start", "T_greedy"))
     assert np.all(_np(sch["cfg_status"]) == 0)
@@ -121,13 +121,22 @@ def test_integer_costs_ragged_segments_and_larger_p(prs, model):
     _check_schedules(prs, host, model, 256, 32)
 
 
-@pytest.mark.parametrize("limits", ["0,0,0,0", "0,0,0,10", "0,0,0", "0,0,1000000000", "0,1000000000,1000000000",
-                                    "1000000000,1000000000,1000000000"])
-def test_uni_every_group_size(prs, limits, monkeypatch):
+_BIG = 1000000000
+# pair-count limits of the 1-, 4- and 16-lane groups, and the binary logarithm of the pair count from which a
+# configuration gets all 64 lanes: every group size in turn gets the whole batch
+_GROUPINGS = {"64 lanes": {"uni_group_pairs": (0, 0, 0), "uni_wave_log2": 1},
+              "64 and 32 lanes": {"uni_group_pairs": (0, 0, 0), "uni_wave_log2": 10},
+              "32 lanes": {"uni_group_pairs": (0, 0, 0)},
+              "16 lanes": {"uni_group_pairs": (0, 0, _BIG)},
+              "4 lanes": {"uni_group_pairs": (0, _BIG, _BIG)},
+              "1 lane": {"uni_group_pairs": (_BIG, _BIG, _BIG)}}
+
+
+@pytest.mark.parametrize("grouping", list(_GROUPINGS))
+def test_uni_every_group_size(prs, grouping):
     """Uni-greedy runs a configuration on 64, 32, 16, 4 or 1 lanes depending on its number of pairs; here every
-    group size gets the same mixed batch (integer and fp64 costs, with fp64 rounding collisions).  A fourth
-    limit is the binary logarithm of the pair count from which a configuration gets all 64 lanes."""
-    monkeypatch.setenv("PRS_UNI_GROUP_WORK", limits)
+    group size gets the same mixed batch (integer and fp64 costs, with fp64 rounding collisions)."""
+    tuning = _GROUPINGS[grouping]
     rng = np.random.default_rng(77)
     n = 96
     p = rng.integers(2, 160, n).astype(np.int32)
@@ -138,16 +147,16 @@ def test_uni_every_group_size(prs, limits, monkeypatch):
     host = prs_inputs.SweepConfigs(p, q, m, rng.integers(1, 12, n).astype(np.int64), rng.integers(0, 4, n).astype(np.int64),
                                    rng.integers(0, 4, n).astype(np.int64), "i64")
     dev = prs.DeviceConfigs.from_host(host)
-    got = prs.simulate_completion_batch(dev, 0, 160, 80)
+    got = prs.simulate_completion_batch(dev, 0, 160, 80, tuning=tuning)
     _sync()
     _check_times(got, O.simulate_batch(host, 0), exact=True)
-    _check_schedules(prs, host, 0, 160, 80)
+    _check_schedules(prs, host, 0, 160, 80, tuning=tuning)
     hostf = prs_inputs.SweepConfigs(p[:40], q[:40], m[:40], np.full(40, 1.0), np.full(40, 0.0), np.full(40, 2.0 ** -52), "f64")
     devf = prs.DeviceConfigs.from_host(hostf)
-    gotf = prs.simulate_completion_batch(devf, 0, 160, 80)
+    gotf = prs.simulate_completion_batch(devf, 0, 160, 80, tuning=tuning)
     _sync()
     assert np.array_equal(_np(gotf["greedy"]), O.simulate_batch(hostf, 0).T_greedy)
-    _check_schedules(prs, hostf, 0, 160, 80)
+    _check_schedules(prs, hostf, 0, 160, 80, tuning=tuning)
 
 
 # --------------------------------------------------------------------------- fp64 sweeps
@@ -206,6 +215,86 @@ def test_fp64_rounding_ties(prs, model):
             ref = O.simulate_batch(host, model)
             assert np.array_equal(_np(got["greedy"]), ref.T_greedy), (q, al, be, ga)
             _check_schedules(prs, host, model, 128, 16)
+
+
+def _mid_machines(cost, seed):
+    """48 machines of 257..1024 processors (the bi-greedy kernel gives each 16 lanes) with 16..64 segments, half
+    of them with a smaller last segment."""
+    rng = np.random.default_rng(seed)
+    n = 48
+    p = rng.integers(257, 1025, n).astype(np.int32)
+    p[:8] = [257, 511, 512, 513, 768, 1000, 1023, 1024]
+    q = rng.integers(16, 65, n).astype(np.int32)
+    per = rng.integers(2, 9, n).astype(np.int64) * (1 if cost == "i64" else 4096)
+    m = q.astype(np.int64) * per
+    m[1::2] -= rng.integers(1, per[1::2])                               # ragged: the last segment is smaller
+    if cost == "i64":
+        al, be, ga = rng.integers(0, 40, n).astype(np.int64), rng.integers(1, 4, n).astype(np.int64), rng.integers(0, 4, n).astype(np.int64)
+    else:
+        al, be, ga = 10.0 ** rng.uniform(-6, -4, n), 10.0 ** rng.uniform(-10, -8, n), 10.0 ** rng.uniform(-11, -9, n)
+    return prs_inputs.SweepConfigs(p, q, m, al, be, ga, cost)
+
+
+@pytest.mark.parametrize("cost", ["i64", "f64"])
+def test_bi_schedules_of_machines_with_hundreds_of_processors(prs, cost):
+    """Bi-greedy schedules pair for pair where a configuration occupies 16 lanes (p = 257..1024) and has many
+    segments in flight: integer and fp64 costs, equal and smaller last segment."""
+    host = _mid_machines(cost, 4242)
+    q_eff = np.array([O.segmentation(int(host.m[i]), int(host.q_req[i]))[0] for i in range(len(host))])
+    assert np.all(q_eff >= 16) and np.any(host.m % host.q_req != 0)
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, 1, 1024, 64)
+    _sync()
+    _check_times(got, O.simulate_batch(host, 1), exact=True)
+    _check_schedules(prs, host, 1, 1024, 64)
+
+
+@pytest.mark.parametrize("entries", [1, 3])
+def test_bi_configurations_handed_over_to_the_general_kernel(prs, entries):
+    """The kernel that runs several configurations per wavefront keeps a short list of running transfers per
+    configuration; one that needs more is rerun by the one-configuration kernel.  With the list cut down to
+    a few entries most of a mixed batch takes that road, times and schedules stay those of the oracle."""
+    rng = np.random.default_rng(31 + entries)
+    n = 90
+    p = rng.integers(2, 400, n).astype(np.int32)
+    p[:6] = [2, 3, 64, 65, 256, 257]
+    q = rng.integers(1, 30, n).astype(np.int32)
+    m = (q.astype(np.int64) * rng.integers(1, 5, n) - rng.integers(0, 2, n)).clip(1)
+    host = prs_inputs.SweepConfigs(p, q, m, rng.integers(0, 12, n).astype(np.int64), rng.integers(1, 4, n).astype(np.int64),
+                                   rng.integers(0, 4, n).astype(np.int64), "i64")
+    tuning = {"bi_list_entries": entries}
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, 1, 512, 32, tuning=tuning)
+    _sync()
+    _check_times(got, O.simulate_batch(host, 1), exact=True)
+    _check_schedules(prs, host, 1, 512, 32, tuning=tuning)
+    hostf = _mid_machines("f64", 99).take(np.arange(0, 48, 4))
+    _check_schedules(prs, hostf, 1, 1024, 64, tuning=tuning)
+
+
+def test_costs_too_large_for_the_cost_type_are_refused(prs):
+    """A configuration whose schedule would pass the range of the cost type (Table I's pipeline time, which
+    bounds every greedy time) is reported as a bad parameter instead of being run: with doubles the sums would
+    reach infinity, which the kernels use as "no value"."""
+    p = np.array([8, 8, 8, 1000], np.int32)
+    q = np.array([1, 1, 4, 4], np.int32)
+    m = np.array([1, 1, 4, 4], np.int64)
+    host = prs_inputs.SweepConfigs(p, q, m, np.array([1e308, 1e299, 1.0, 1e298]), np.zeros(4), np.zeros(4), "f64")
+    dev = prs.DeviceConfigs.from_host(host)
+    for model in (0, 1):
+        got = prs.simulate_completion_batch(dev, model, 1024, 8)
+        _sync()
+        assert list(_np(got["cfg_status"])) == [1, 0, 0, 1]
+        g = _np(got["greedy"])
+        assert np.isnan(g[0]) and np.isnan(g[3]) and g[1] == 3e299 and np.isfinite(g[2])
+    hosti = prs_inputs.SweepConfigs(p, q, m, np.array([1 << 61, 1 << 58, 1, 1 << 52], np.int64), np.ones(4, np.int64),
+                                    np.zeros(4, np.int64), "i64")
+    got = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(hosti), 0, 1024, 8)
+    _sync()
+    assert list(_np(got["cfg_status"])) == [1, 0, 0, 1] and _np(got["greedy"])[1] == 3 * ((1 << 58) + 1)
+    off = prs.prs_pair_offsets(dev, 1024, 8)
+    _sync()
+    assert list(_np(off)) == [0, 0, 7, 35, 35]
 
 
 def test_invalid_configurations_are_reported_not_fatal(prs):
@@ -285,18 +374,64 @@ def test_full_sweep_invariants_and_samples(prs, model):
     assert _rel_ok(_np(got["butterfly"])[idx], ref.T_butterfly) and _rel_ok(_np(got["revopt"])[idx], ref.T_revopt)
 
 
-@pytest.mark.parametrize("model", [0, 1])
-def test_large_p_sample(prs, model):
-    full = prs_inputs.large_p_sweep(2000)
-    work = full.p.astype(np.float64) ** 2 * full.q_req
-    idx = np.argsort(work)[: (6 if model == 0 else 3)]
+def _large_p_subsample(max_pairs):
+    """Every 61st configuration of the large-machine sweep (p in [1024, 65536], 64 to 4096 segments) whose
+    schedule has at most max_pairs pairs, plus the first few with more than 32768 processors."""
+    full = prs_inputs.large_p_sweep()
+    q = np.array([O.segmentation(int(full.m[i]), int(full.q_req[i]))[0] for i in range(len(full))])
+    pairs = (full.p.astype(np.int64) - 1) * q
+    every = np.arange(0, len(full), 61)
+    wide = np.nonzero((full.p > 32768) & (pairs <= max_pairs))[0][:6]
+    idx = np.unique(np.concatenate([every[pairs[every] <= max_pairs], wide]))
+    assert np.any(full.p[idx] > 32768) and len(idx) >= 60
+    return full, idx
+
+
+def test_large_machines_uni_times(prs):
+    """Uni-greedy completion times on the large-machine sweep against the oracle's value-only form of
+    Algorithm 1, bit for bit (same roundings), tens of thousands of processors included."""
+    from concurrent.futures import ThreadPoolExecutor
+    full, idx = _large_p_subsample(3e7)
     host = full.take(idx)
     dev = prs.DeviceConfigs.from_host(host)
-    got = prs.simulate_completion_batch(dev, model, 65536, 4096)
+    got = prs.simulate_completion_batch(dev, 0, 65536, 4096)
     _sync()
-    ref = O.simulate_batch(host, model)
-    assert np.array_equal(_np(got["greedy"]), ref.T_greedy)
     assert np.all(_np(got["cfg_status"]) == 0)
+
+    def one(i):
+        return O.uni_greedy_time(int(host.p[i]), O.equi_sizes(int(host.m[i]), int(host.q_req[i])), float(host.alpha[i]),
+                                 float(host.beta[i]), float(host.gamma[i]), "f64")
+    with ThreadPoolExecutor(16) as ex:
+        ref = np.array(list(ex.map(one, range(len(host)))))
+    assert np.array_equal(_np(got["greedy"]), ref)
+    assert np.all(ref <= _np(got["pipeline"]) * (1 + 1e-12)) and np.all(ref <= _np(got["binary"]) * (1 + 1e-12))   # Theorem 1
+
+
+def test_large_machines_bi_times(prs):
+    """Bi-greedy on the large-machine sweep.  (i) The draws of the subsample with the message size rounded up to
+    a multiple of the segment count (equal segments): the time is that of the reversed optimal broadcast, Table
+    III, up to 65536 processors.  (ii) Every 16th of the cheapest tenth of the sweep as drawn (mostly a smaller
+    last segment) against the oracle, bit for bit."""
+    full, idx = _large_p_subsample(1.2e7)
+    host = full.take(idx)
+    sz = -(-host.m // host.q_req)
+    host.m = sz * host.q_req
+    dev = prs.DeviceConfigs.from_host(host)
+    got = prs.simulate_completion_batch(dev, 1, 65536, 4096)
+    _sync()
+    assert np.all(_np(got["cfg_status"]) == 0) and np.array_equal(_np(got["q_eff"]), host.q_req)
+    L = np.ceil(np.log2(host.p)).astype(np.int64)
+    r = (host.alpha + host.beta * sz) + host.gamma * sz
+    assert _rel_ok(_np(got["greedy"]), (L + host.q_req - 1) * r, 1e-11)
+    assert _rel_ok(_np(got["greedy"]), _np(got["revopt"]), 1e-11)
+    work = full.p.astype(np.float64) ** 2 * full.q_req
+    cheap = np.sort(np.argsort(work)[: len(full) // 10])[::16]
+    small = full.take(cheap)
+    got = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(small), 1, 65536, 4096)
+    _sync()
+    ref = O.simulate_batch(small, 1)
+    assert np.array_equal(_np(got["greedy"]), ref.T_greedy) and np.all(_np(got["cfg_status"]) == 0)
+    assert np.any(small.m % (-(-small.m // small.q_req)) != 0)
 
 
 @pytest.mark.parametrize("model", [0, 1])
@@ -456,13 +591,12 @@ def test_butterfly_threshold_by_bisection(prs, p):
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 
 
-@pytest.mark.parametrize("limits", [None, "0,0,0,0", "0,0,0", "0,0,1000000000", "0,1000000000,1000000000"])
+@pytest.mark.parametrize("grouping", [None, "64 lanes", "32 lanes", "16 lanes", "4 lanes"])
 @pytest.mark.parametrize("cost", ["i64", "f64"])
-def test_unequal_segmentation_matches_the_oracle(prs, cost, limits, monkeypatch):
+def test_unequal_segmentation_matches_the_oracle(prs, cost, grouping):
     """Every segmentation of short messages of mixed length through uni-greedy, at every group size: all
     2^(m-1) times and the per-problem summary against the oracle running the segmentations one by one."""
-    if limits is not None:
-        monkeypatch.setenv("PRS_UNI_GROUP_WORK", limits)
+    tuning = None if grouping is None else _GROUPINGS[grouping]
     rng = np.random.default_rng(808)
     n = 36
     p = rng.integers(2, 70, n).astype(np.int32)
@@ -479,7 +613,7 @@ def test_unequal_segmentation_matches_the_oracle(prs, cost, limits, monkeypatch)
     host = prs_inputs.SweepConfigs(p, np.zeros(n, np.int32), m, al, be, ga, cost)
     dev = prs.DeviceConfigs.from_host(host)
     m_max = 9
-    got = prs.unequal_segmentation_batch(dev, 70, m_max)
+    got = prs.unequal_segmentation_batch(dev, 70, m_max, tuning=tuning)
     _sync()
     st = _np(got["cfg_status"])
     T_all = _np(got["T_all"])

@@ -132,6 +132,40 @@ def test_uni_fp64_matches_value_only_restatement():
         assert s.T == _multiset_uni(p, c, gg)
 
 
+def test_uni_value_only_form_equals_algorithm_1():
+    """The heap form (ready times only) against Algorithm 1 with its two scans: the whole integer sweep, the
+    segmentations of Table IV's rows (unequal sizes), fp64 costs with rounding ties; and, where the two scans
+    would take too long, against what the paper fixes for any p: one segment is the binomial tree (Section 5.2,
+    Table I), Theorem 1 and Table II."""
+    cfg = prs_inputs.tiny_sweep()
+    for i in range(len(cfg)):
+        p, q, a, g = int(cfg.p[i]), int(cfg.q_req[i]), int(cfg.alpha[i]), int(cfg.gamma[i])
+        assert O.uni_greedy_time(p, [1] * q, a, 1, g) == O.uni_greedy(p, [1] * q, a, 1, g, want_schedule=False).T
+    for p, a, g, _, equi, opts in _table4_rows():
+        if p > 200:
+            continue
+        for sizes in [equi] + opts[:2]:
+            assert O.uni_greedy_time(p, list(sizes), a, 1, g) == O.uni_greedy(p, list(sizes), a, 1, g, want_schedule=False).T
+    full = prs_inputs.uni_sweep(600)
+    for i in range(0, 600, 5):
+        p, m, qr = int(full.p[i]), int(full.m[i]), int(full.q_req[i])
+        if p * p * qr > 2e7:
+            continue
+        sizes = O.equi_sizes(m, qr)
+        a, b, g = float(full.alpha[i]), float(full.beta[i]), float(full.gamma[i])
+        assert O.uni_greedy_time(p, sizes, a, b, g, "f64") == O.uni_greedy(p, sizes, a, b, g, "f64", want_schedule=False).T
+    for al, be, ga in [(1.0, 0.0, 2.0 ** -52), (0.75, 2.0 ** -54, 2.0 ** -51)]:       # sums that collide in rounding
+        for p in (5, 17, 64):
+            sizes = O.equi_sizes(29, 9)
+            assert O.uni_greedy_time(p, sizes, al, be, ga, "f64") == O.uni_greedy(p, sizes, al, be, ga, "f64", want_schedule=False).T
+    for p in (1024, 4097, 40000, 65536):
+        L = math.ceil(math.log2(p))
+        assert O.uni_greedy_time(p, [1000], 7, 2, 3) == L * (7 + 2000 + 3000)
+        T = O.uni_greedy_time(p, [5] * 12, 3, 1, 2)
+        cf = O.closed_forms(O.UNI, p, 12, 60, 5, 3, 1, 2)
+        assert L * 3 <= T <= min(cf["pipeline"], cf["binary"]) and T >= 2 * 60 * 1 and T >= (L + 11) * 3
+
+
 def test_uni_no_slower_than_in_order_baselines_and_above_bounds():
     # pipeline and binary reduce segments in order, so Theorem 1 bounds uni-greedy by both
     # (Table I); Table II gives the lower bounds of any reduction.
