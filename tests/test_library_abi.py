@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(prs.binding.EXPORTS) == names
-    assert lib.prs_abi_version() == 1
+    assert lib.prs_abi_version() == 2
 
 
 def test_workspace_sizes_are_monotone_and_bounded():
@@ -48,10 +48,10 @@ def test_calls_reject_bad_arguments_before_touching_the_gpu():
     lib = prs.load_library()
     cfg = prs.binding._Configs(0, 0, 0, 0, 0, 0)
     out = prs.binding._Unequal(*([None] * 8))
-    rc = lib.unequal_segmentation_batch(C.byref(cfg), 4, prs.PRS_COST_I64, 64, 10, C.byref(out), None, 0, None)
+    rc = lib.unequal_segmentation_batch(C.byref(cfg), 4, prs.PRS_COST_I64, 64, 10, C.byref(out), None, 0, None, None)
     assert rc == 1                                                  # PRS_EINVAL: null arrays with n > 0
-    assert lib.unequal_segmentation_batch(C.byref(cfg), 0, prs.PRS_COST_I64, 64, 30, C.byref(out), None, 0, None) == 1
-    assert lib.unequal_segmentation_batch(C.byref(cfg), 0, prs.PRS_COST_I64, 64, 10, C.byref(out), None, 0, None) == 0
+    assert lib.unequal_segmentation_batch(C.byref(cfg), 0, prs.PRS_COST_I64, 64, 30, C.byref(out), None, 0, None, None) == 1
+    assert lib.unequal_segmentation_batch(C.byref(cfg), 0, prs.PRS_COST_I64, 64, 10, C.byref(out), None, 0, None, None) == 0
     # replay: unknown element type or operation
     off = (C.c_int64 * 2)(0, 8)
     one = C.c_void_p(256)                                            # never dereferenced: the call fails first
