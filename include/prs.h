@@ -187,6 +187,25 @@ int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset,
                      void *out, int32_t *status,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * replay_reduction for callers that can neither allocate device memory nor
+ * bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, results and status as
+ * replay_reduction, without `workspace`: the tree programs live in a fixed
+ * device array of 8 MiB inside the library, one per GPU, taken hold of at the
+ * first call on that GPU and kept until the process ends.  The call itself
+ * allocates nothing.  Returns PRS_ENOSPC (nothing enqueued) when the schedule
+ * needs more than the array holds: 8(q+1) + 4pq + 768 bytes rounded up to
+ * multiples of 256, plus 32pq bytes when p > 1536.  All calls on one GPU
+ * share that array: two of them must not be in flight at the same time (on
+ * different streams, or from different threads); calls that follow each other
+ * on one stream are fine.
+ */
+int replay_reduction_static(int32_t p, int32_t q, const int64_t *seg_elem_offset,
+                            const int32_t *src, const int32_t *dst, const int32_t *seg, int64_t n_pairs,
+                            const void *in, int64_t stride_elems, int64_t n_elems, int dtype,
+                            void *out, int32_t *status, void *stream);
+
 /* Result columns of optimal_segmentation_batch, DEVICE pointers to n entries
  * each, any of them may be NULL.  T_* have the cost type of the call. */
 typedef struct prs_best {

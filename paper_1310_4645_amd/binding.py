@@ -22,7 +22,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("prs_abi_version", "prs_workspace_bytes", "simulate_completion_batch", "prs_pair_offsets",
-           "greedy_schedule_batch", "replay_reduction", "optimal_segmentation_batch", "unequal_segmentation_batch")
+           "greedy_schedule_batch", "replay_reduction", "replay_reduction_static", "optimal_segmentation_batch",
+           "unequal_segmentation_batch")
 
 
 class PrsError(RuntimeError):
@@ -95,6 +96,9 @@ def load_library():
         lib.replay_reduction.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                          C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.replay_reduction_static.restype = C.c_int
+        lib.replay_reduction_static.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.optimal_segmentation_batch.restype = C.c_int
         lib.optimal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
                                                    C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
@@ -299,4 +303,23 @@ def replay_reduction(p: int, q: int, seg_elem_offset, src, dst, seg, inp, out=No
                               _dp(inp), int(inp.stride(0)), n_elems, dtype, _dp(out), _dp(status),
                               C.c_void_p(_aligned_ptr(ws)), ws.numel() - (_aligned_ptr(ws) - ws.data_ptr()), _stream())
     _check(rc, "replay_reduction")
+    return out, status
+
+
+def replay_reduction_static(p: int, q: int, seg_elem_offset, src, dst, seg, inp, out, status, op=PRS_OP_SUM):
+    """replay_reduction without a workspace and without any allocation: `out` ([n_elems], dtype of inp) and
+    `status` (one int32) are the caller's device tensors.  Raises PrsError (PRS_ENOSPC) for schedules beyond the
+    library's fixed scratch array."""
+    import torch
+    lib = load_library()
+    off = np.ascontiguousarray(seg_elem_offset, dtype=np.int64)
+    n_elems = int(inp.shape[1])
+    assert inp.stride(1) == 1
+    kinds = {torch.int32: PRS_I32, torch.float32: PRS_F32, torch.float64: PRS_F64, torch.int64: PRS_I64}
+    if inp.dtype not in kinds:
+        raise PrsError(f"replay_reduction_static: unsupported element type {inp.dtype}")
+    rc = lib.replay_reduction_static(p, q, off.ctypes.data_as(C.c_void_p), _dp(src), _dp(dst), _dp(seg), int(src.shape[0]),
+                                     _dp(inp), int(inp.stride(0)), n_elems, kinds[inp.dtype] | op, _dp(out), _dp(status),
+                                     _stream())
+    _check(rc, "replay_reduction_static")
     return out, status

@@ -623,6 +623,37 @@ int greedy_schedule_batch(const prs_configs *cfg, int64_t n, int model, int cost
     return run_greedy(PRS_CALL_SCHEDULE, cfg, n, model, cost, p_max, q_max, t, s, workspace, workspace_bytes, stream, tuning);
 }
 
+// argument checks shared by the two replay entry points
+static int replay_bad_arguments(int32_t p, int32_t q, const int64_t *seg_elem_offset, const int32_t *src, const int32_t *dst,
+                                const int32_t *seg, int64_t n_pairs, const void *in, int64_t stride_elems, int64_t n_elems,
+                                int dtype, const void *out)
+{
+    if (p < 2 || p > 4096 || q < 1 || q > 65536 || !seg_elem_offset || !src || !dst || !seg || !in || !out) return PRS_EINVAL;
+    if (n_pairs != static_cast<int64_t>(p - 1) * q || n_pairs >= (INT64_C(1) << 31)) return PRS_EINVAL;
+    const int elem = dtype & 0xFF, op = dtype & ~0xFF;
+    if ((elem != PRS_I32 && elem != PRS_F32 && elem != PRS_F64 && elem != PRS_I64) || (op != PRS_OP_SUM && op != PRS_OP_MAX))
+        return PRS_EINVAL;
+    if (n_elems < 0 || stride_elems < n_elems) return PRS_EINVAL;
+    if (seg_elem_offset[0] != 0 || seg_elem_offset[q] != n_elems) return PRS_EINVAL;
+    for (int k = 0; k < q; ++k)
+        if (seg_elem_offset[k + 1] < seg_elem_offset[k]) return PRS_EINVAL;
+    return PRS_OK;
+}
+
+int replay_reduction_static(int32_t p, int32_t q, const int64_t *seg_elem_offset, const int32_t *src, const int32_t *dst,
+                            const int32_t *seg, int64_t n_pairs, const void *in, int64_t stride_elems, int64_t n_elems,
+                            int dtype, void *out, int32_t *status, void *stream)
+{
+    const int bad = replay_bad_arguments(p, q, seg_elem_offset, src, dst, seg, n_pairs, in, stride_elems, n_elems, dtype, out);
+    if (bad != PRS_OK) return bad;
+    if (replay_scratch_bytes(p, q) > kReplayStaticBytes) return PRS_ENOSPC;       // too many processors x segments for the fixed array
+    void *ws = nullptr;
+    if (replay_static_scratch(&ws) != hipSuccess) return PRS_EDEVICE;
+    ReplayLaunch L{p, q, seg_elem_offset, src, dst, seg, n_pairs, in, stride_elems, n_elems, dtype & 0xFF, dtype & ~0xFF, out, status,
+                   static_cast<char *>(ws), static_cast<hipStream_t>(stream)};
+    return launch_replay(L) == hipSuccess ? PRS_OK : PRS_EDEVICE;
+}
+
 int replay_reduction(int32_t p, int32_t q, const int64_t *seg_elem_offset, const int32_t *src, const int32_t *dst,
                      const int32_t *seg, int64_t n_pairs, const void *in, int64_t stride_elems, int64_t n_elems, int dtype,
                      void *out, int32_t *status, void *workspace, size_t workspace_bytes, void *stream)

@@ -100,6 +100,10 @@ struct ReplayLaunch {
 };
 size_t replay_workspace_bytes(int32_t p, int32_t q);
 hipError_t launch_replay(const ReplayLaunch &L);
+// replay without a caller's workspace: a fixed device array per GPU
+constexpr size_t kReplayStaticBytes = static_cast<size_t>(8) << 20;
+size_t replay_scratch_bytes(int32_t p, int32_t q);          // what a replay touches of its scratch memory
+hipError_t replay_static_scratch(void **ptr);                // address of the current device's array
 
 struct OffsetsLaunch {
     ConfigArrays cfg;

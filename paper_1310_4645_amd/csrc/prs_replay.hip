@@ -17,6 +17,8 @@
 // "load the processor's element; if push, save the running sum and start a new
 // one from the loaded value, else add it to the running sum; then npop times
 // add the running sum into the last saved one".
+#include <mutex>
+
 #include "prs_device.h"
 #include "prs_launch.h"
 
@@ -36,10 +38,21 @@ struct ReplayWs {
 
 __host__ __device__ inline size_t rp_align(size_t v) { return (v + 255) / 256 * 256; }
 
+// The builder's work arrays (eight of p entries per segment) sit in LDS up to this many processors, beyond it in
+// the scratch memory.
+constexpr int32_t kBuildLdsProcs = 48 * 1024 / (8 * 4);
+
 size_t replay_workspace_bytes(int32_t p, int32_t q)
 {
     const size_t P = static_cast<size_t>(p), Q = static_cast<size_t>(q);
-    return rp_align((Q + 1) * 8) + rp_align(Q * P * 4) + rp_align(Q * P * 4 * 8) + 256;
+    return rp_align((Q + 1) * 8) + rp_align(Q * P * 4) + 256 + rp_align(Q * P * 4 * 8);
+}
+
+// What a replay really touches of its scratch memory: the builder's arrays only for machines too large for LDS.
+size_t replay_scratch_bytes(int32_t p, int32_t q)
+{
+    const size_t P = static_cast<size_t>(p), Q = static_cast<size_t>(q);
+    return rp_align((Q + 1) * 8) + rp_align(Q * P * 4) + 256 + (p > kBuildLdsProcs ? rp_align(Q * P * 4 * 8) : 0);
 }
 
 static ReplayWs carve_replay(char *ws, int32_t p, int32_t q)
@@ -48,9 +61,35 @@ static ReplayWs carve_replay(char *ws, int32_t p, int32_t q)
     ReplayWs w;
     w.offsets = reinterpret_cast<int64_t *>(ws); ws += rp_align((Q + 1) * 8);
     w.prog = reinterpret_cast<uint32_t *>(ws); ws += rp_align(Q * P * 4);
-    w.tmp = reinterpret_cast<int32_t *>(ws); ws += rp_align(Q * P * 4 * 8);
-    w.flags = reinterpret_cast<int32_t *>(ws);
+    w.flags = reinterpret_cast<int32_t *>(ws); ws += 256;
+    w.tmp = reinterpret_cast<int32_t *>(ws);
     return w;
+}
+
+// Scratch memory for callers that cannot allocate: one array per GPU, held from the first use on that GPU until the
+// process ends.  The name `scratch` is only a handle on the host; kernels get the address hipGetSymbolAddress
+// returns for the current device.
+static __device__ __align__(256) unsigned char scratch[kReplayStaticBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+hipError_t replay_static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 __global__ void replay_clear_flags(int32_t *flags) { if (threadIdx.x < 3) flags[threadIdx.x] = 0; }
@@ -390,7 +429,7 @@ hipError_t launch_replay(const ReplayLaunch &L)
     }
     hipLaunchKernelGGL(replay_clear_flags, dim3(1), dim3(64), 0, L.stream, w.flags);
     const size_t build_lds = static_cast<size_t>(L.p) * 8 * 4;
-    if (build_lds <= 48 * 1024)
+    if (L.p <= kBuildLdsProcs)
         hipLaunchKernelGGL(replay_build<true>, dim3(static_cast<unsigned>(L.q)), dim3(kBuildThreads), build_lds, L.stream, L.p, L.q,
                            L.src, L.dst, L.seg, L.n_pairs, w.prog, w.tmp, w.flags);
     else
