@@ -45,6 +45,7 @@ def lib():
         for suf in ("_i64", "_f64"):
             getattr(_lib, "orc_binomial_construct" + suf).restype = C.c_int64 if suf == "_i64" else C.c_double
             getattr(_lib, "orc_pipeline_construct" + suf).restype = C.c_int64 if suf == "_i64" else C.c_double
+            getattr(_lib, "orc_binary_construct" + suf).restype = C.c_int64 if suf == "_i64" else C.c_double
             getattr(_lib, "orc_butterfly_steps" + suf).restype = C.c_double
     return _lib
 
@@ -171,6 +172,15 @@ def pipeline_construct(p, sizes, alpha, beta, gamma, cost="i64"):
     sizes = np.ascontiguousarray(sizes, dtype=np.int64)
     return getattr(lib(), "orc_pipeline_construct" + suf)(C.c_int32(p), C.c_int32(sizes.shape[0]), _ptr(sizes, C.c_int64),
                                                           ct(alpha), ct(beta), ct(gamma))
+
+
+def binary_construct(model, p, sizes, alpha, beta, gamma, cost="i64"):
+    """Completion time of the binary tree of Section 4 built pair by pair (heap-shaped tree, two senders per
+    receiver in turn, segments in order), under either port model."""
+    _, ct, suf = _ct(cost)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int64)
+    return getattr(lib(), "orc_binary_construct" + suf)(C.c_int(model), C.c_int32(p), C.c_int32(sizes.shape[0]),
+                                                        _ptr(sizes, C.c_int64), ct(alpha), ct(beta), ct(gamma))
 
 
 def butterfly_steps(p, m, alpha, beta, gamma, cost="f64"):

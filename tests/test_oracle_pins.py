@@ -497,6 +497,37 @@ def test_constructions_match_closed_forms_where_exact():
         assert got == pytest.approx(O.closed_forms(O.BI, p, 1, 1 << 20, 1 << 20, 3e-6, 2e-9, 5e-10, "f64")["butterfly"], rel=1e-13)
 
 
+def test_binary_tree_built_in_steps_meets_the_tables():
+    """Section 4's binary tree built step by step (two senders per receiver in turn, extra processors first)
+    and timed with the cost model: Table I's (2(N-1) + 4(q-1)) r with one port and, with two ports,
+    2(N+q-2) r -- the form Table III's own optimal-size rows follow from, not the printed 2(N+q-1) r.  Equal for
+    p = 2^n - 1 (the case the section describes) whatever the combine cost, never above the table for any
+    p > 3 or with a smaller last segment (the tables' note: upper bounds then)."""
+    for a, b, g in COSTS:
+        for q in (1, 2, 3, 7):
+            for p in (7, 15, 31, 63, 127):
+                for model in (O.UNI, O.BI):
+                    cf = O.closed_forms(model, p, q, 3 * q, 3, a, b, g)["binary"]
+                    assert O.binary_construct(model, p, [3] * q, a, b, g) == cf, (model, p, q, a, b, g)
+            r = a + 3 * b + 3 * g
+            assert O.binary_construct(O.BI, 31, [3] * q, a, b, g) == 2 * (5 + q - 2) * r
+            if r > 0:
+                assert O.binary_construct(O.BI, 31, [3] * q, a, b, g) < 2 * (5 + q - 1) * r        # not the printed form
+            for p in (4, 5, 6, 9, 12, 20, 33, 100):
+                for model in (O.UNI, O.BI):
+                    cf = O.closed_forms(model, p, q, 3 * q, 3, a, b, g)["binary"]
+                    assert O.binary_construct(model, p, [3] * q, a, b, g) <= cf
+                    if q > 1:
+                        assert O.binary_construct(model, p, [3] * (q - 1) + [1], a, b, g) <= cf
+    # uni-greedy is never slower than this in-order tree either (Theorem 1)
+    for p in (7, 20, 63):
+        for q in (1, 4):
+            assert O.uni_greedy(p, [3] * q, 2, 1, 1, want_schedule=False).T <= O.binary_construct(O.UNI, p, [3] * q, 2, 1, 1)
+    # fp64: same value up to the rounding of a product against a running sum
+    got = O.binary_construct(O.UNI, 63, [4096] * 9, 3e-6, 2e-9, 5e-10, "f64")
+    assert got == pytest.approx(O.closed_forms(O.UNI, 63, 9, 9 * 4096, 4096, 3e-6, 2e-9, 5e-10, "f64")["binary"], rel=1e-13)
+
+
 # --------------------------------------------------------------------------- replay
 def test_replay_int32_equals_plain_sum_and_fp32_is_close():
     # Section 1: the pieces "need to be combined using an associative operation to form the
