@@ -8,6 +8,13 @@ under both models (greedy_schedule_batch), and the replay of the p = 256,
 64-segment uni-greedy schedule over 256 buffers of 2^22 elements, once int32 and
 once fp32 (replay_reduction).  Inputs are resident in HBM before the timed
 region.  One JSON line is printed.
+
+Outside the timed step, reported in the same line: the large-machine sweep
+(p in [1024, 65536], 64 to 4096 segments; every 16th of its 10,000
+configurations, completion times under both models), the register-only
+microkernel that gives the practical ceiling of Algorithm 1's arithmetic, plain
+device copy and read passes, the best-segmentation search, the unequal-
+segmentation experiment, and the CPU oracle on a bounded sample.
 """
 from __future__ import annotations
 
@@ -37,8 +44,9 @@ OPS_PER_PAIR_UNI = 4
 OPS_PER_PAIR_BI = 10
 
 
-def cpu_baseline(host, seconds_hint=20.0):
-    """The oracle as it stands on this machine's cores, on a prefix of the same sweep."""
+def cpu_baseline(host, large):
+    """The oracle as it stands on this machine's cores, on a prefix of the same sweep; next to it the same on one
+    core (a shorter prefix) and a few configurations of the large-machine sweep."""
     from concurrent.futures import ThreadPoolExecutor
 
     import oracle
@@ -56,19 +64,58 @@ def cpu_baseline(host, seconds_hint=20.0):
     with ThreadPoolExecutor(cores) as ex:
         list(ex.map(one, idx, chunksize=4))
     dt = time.perf_counter() - t0
+    one_sample = 96
+    t1 = time.perf_counter()
+    for i in range(one_sample):
+        one(i)
+    dt1 = time.perf_counter() - t1
+    # large machines: the value-only form of Algorithm 1 and Algorithm 2 on the cheapest of the timed subsample
+    pick = np.argsort(large.p.astype(np.float64) ** 2 * large.q_req)[:cores]
+
+    def big(i):
+        sizes = oracle.equi_sizes(int(large.m[i]), int(large.q_req[i]))
+        a, b, g = float(large.alpha[i]), float(large.beta[i]), float(large.gamma[i])
+        oracle.uni_greedy_time(int(large.p[i]), sizes, a, b, g, "f64")
+        oracle.bi_greedy(int(large.p[i]), sizes, a, b, g, "f64", mode=oracle.MODE_EVENT | oracle.MODE_PRUNE, want_schedule=False)
+        return (int(large.p[i]) - 1) * len(sizes)
+
+    t2 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        big_pairs = sum(ex.map(big, pick))
+    dt2 = time.perf_counter() - t2
     return {"value": 2 * sample / dt, "unit": "schedules/s", "cores": cores, "kind": "oracle",
             "sample": f"first {sample} configurations of the 100,000-configuration sweep, uni-greedy and bi-greedy "
-                      f"completion times with baselines, {dt:.1f} s of wall time"}
+                      f"completion times with baselines, {dt:.1f} s of wall time",
+            "one_core": {"value": 2 * one_sample / dt1, "unit": "schedules/s", "cores": 1,
+                         "sample": f"first {one_sample} configurations of the same sweep, {dt1:.1f} s"},
+            "large_machines": {"value": 2 * len(pick) / dt2, "unit": "schedules/s", "pairs_per_s": 2 * big_pairs / dt2, "cores": cores,
+                               "sample": f"the {len(pick)} cheapest configurations of the timed large-machine subsample "
+                                         f"(value-only uni-greedy, bi-greedy), {dt2:.1f} s"}}
 
 
 SEARCH_PROBLEMS = 10000
 
-# profiles/sweep100k_sq_instruction_counters.txt
-PROFILED_VALU_BUSY = {"simulate_uni": 0.32, "simulate_bi": 0.36, "schedule_uni": 0.20, "schedule_bi": 0.30}
+COUNTER_FILE = os.path.join("profiles", "sweep100k_and_replay_counters_per_call.txt")
 
-# per-launch HBM traffic measured with rocprofv3 (profiles/replay256x4Mi_and_sweep100k_hbm_bytes.txt)
-PROFILED_TRAFFIC_BYTES = {"simulate_uni": 1.02e10, "simulate_bi": 5.8e8, "schedule_uni": 8.80e10, "schedule_bi": 2.58e10,
-                          "replay_i32": 4.33e9, "replay_f32": 4.33e9}
+
+def profiled_counters():
+    """Per call of the step: HBM bytes per launch and share of the VALU issue slots, as summarised from rocprofv3
+    counter runs in COUNTER_FILE (lines `call hbm_bytes valu_busy`); nothing is measured here.  Empty if the file
+    is missing."""
+    table = {}
+    try:
+        with open(os.path.join(ROOT, COUNTER_FILE)) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and not line.startswith("#"):
+                    table[parts[0]] = (float(parts[1]), float(parts[2]))
+    except OSError:
+        pass
+    return table
+
+
+LARGE_EVERY = 16
+LARGE_P_MAX, LARGE_Q_MAX = 65536, 4096
 
 
 def main():
@@ -133,6 +180,7 @@ def main():
     torch.cuda.synchronize()
 
     names = ["simulate_uni", "simulate_bi", "schedule_uni", "schedule_bi", "replay_i32", "replay_f32"]
+    held = {}                                    # what the calls of the last step returned
 
     def step(events=None):
         def mark(k):
@@ -145,15 +193,15 @@ def main():
         prs.simulate_completion_batch(dev, prs.PRS_BI, P_MAX, Q_MAX, out=times[prs.PRS_BI],
                                       workspace=ws[(prs.PRS_CALL_SIMULATE, prs.PRS_BI)])
         mark(2)
-        prs.greedy_schedule_batch(dev, prs.PRS_UNI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
-                                  workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI)])
+        held["su"] = prs.greedy_schedule_batch(dev, prs.PRS_UNI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
+                                               workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_UNI)])
         mark(3)
-        prs.greedy_schedule_batch(dev, prs.PRS_BI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
-                                  workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_BI)])
+        held["sb"] = prs.greedy_schedule_batch(dev, prs.PRS_BI, P_MAX, Q_MAX, off, n_pairs, src, dst, seg, tst,
+                                               workspace=ws[(prs.PRS_CALL_SCHEDULE, prs.PRS_BI)])
         mark(4)
-        prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_i, out=out_i, workspace=rws)
+        held["ri"] = prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_i, out=out_i, workspace=rws)
         mark(5)
-        prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_f, out=out_f, workspace=rws)
+        held["rf"] = prs.replay_reduction(REPLAY_P, REPLAY_Q, seg_off, rsch["src"], rsch["dst"], rsch["seg"], buf_f, out=out_f, workspace=rws)
         mark(6)
 
     if args.copy_probe:
@@ -175,9 +223,19 @@ def main():
     part_ms = {nm: float(np.mean([ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)]))
                for k, nm in enumerate(names)}
 
-    # sanity of what was timed: all configurations valid, replay finished
+    last = {"replay_status": [int(held["ri"][1].item()), int(held["rf"][1].item())],
+            "sched_status_bad": [int((held[k]["cfg_status"] != 0).sum().item()) for k in ("su", "sb")],
+            "T_equal": [bool(torch.equal(held["su"]["T_greedy"], times[prs.PRS_UNI]["greedy"])),
+                        bool(torch.equal(held["sb"]["T_greedy"], times[prs.PRS_BI]["greedy"]))],
+            "bi_src_range": [int(src.min().item()), int(src.max().item())]}
+    # sanity of what was timed: all configurations valid, schedules complete and in range, replay finished
     assert int((times[prs.PRS_UNI]["cfg_status"] != 0).sum().item()) == 0
     assert int((times[prs.PRS_BI]["cfg_status"] != 0).sum().item()) == 0
+    assert last["replay_status"] == [0, 0], last["replay_status"]
+    assert last["sched_status_bad"] == [0, 0]
+    # the schedule call returns the same completion times as the simulate call, and processor indices of a machine
+    assert last["T_equal"] == [True, True]
+    assert last["bi_src_range"][0] >= 1 and last["bi_src_range"][1] <= P_MAX - 1
 
     # roofline of the dominant kernel (the launch that takes the largest share of the step)
     dominant = max(part_ms, key=part_ms.get)
@@ -189,13 +247,14 @@ def main():
         roof = {"bound": "alu", "achieved": ops / (part_ms[dominant] * 1e-3) / 1e12, "peak": PEAK_FP64_OPS / 1e12,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    # HBM bytes per launch of that call's kernel, from the rocprofv3 counter runs summarised under profiles/
-    # (FETCH_SIZE and WRITE_SIZE, scaled by what they read for a 1 GiB copy); None where not collected
-    roof["traffic"] = PROFILED_TRAFFIC_BYTES.get(dominant)
+    # HBM bytes per launch of that call's kernel and the share of the chip's VALU issue slots it uses: not measured
+    # in this run but read from the rocprofv3 counter summary named here (FETCH_SIZE and WRITE_SIZE scaled by what
+    # they read for a plain copy; SQ_INSTS_VALU x 4 cycles / (1024 SIMDs x launch time x 2.4 GHz)); None if absent
+    prof = profiled_counters()
+    roof["traffic"] = prof.get(dominant, (None, None))[0]
     roof["kernel"] = dominant
-    # share of the chip's VALU issue slots the call's kernel uses, from the SQ counter run summarised under profiles/
-    # (SQ_INSTS_VALU x 4 cycles / (1024 SIMDs x launch time x 2.4 GHz)); None where not collected
-    roof["valu_busy_profiled"] = PROFILED_VALU_BUSY.get(dominant)
+    roof["valu_busy_profiled"] = prof.get(dominant, (None, None))[1]
+    roof["counters_from"] = COUNTER_FILE if prof else None
     replay_bytes = 4.0 * REPLAY_N * (REPLAY_P + 1)
     out = {
         "metric": "greedy schedules simulated/sec (uni+bi, p<=65536) + replay HBM GB/s vs peak",
@@ -215,7 +274,7 @@ def main():
                    "f32_GBps": replay_bytes / (part_ms["replay_f32"] * 1e-3) / 1e9,
                    "peak_GBps": PEAK_HBM / 1e9, "algorithmic_bytes": replay_bytes,
                    "frac_of_peak": replay_bytes / (min(part_ms["replay_i32"], part_ms["replay_f32"]) * 1e-3) / PEAK_HBM,
-                   "traffic": PROFILED_TRAFFIC_BYTES["replay_f32"],
+                   "traffic": prof.get("replay_f32", (None, None))[0],
                    "note": "whole replay_reduction call (schedule check and program build included)"},
         "schedule_emission_GBps": {"uni": n_pairs * 20.0 / (part_ms["schedule_uni"] * 1e-3) / 1e9,
                                    "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
@@ -238,6 +297,37 @@ def main():
     buf_i.copy_(buf_f.view(i32))                                         # warm-up; buf_i is no longer needed
     out["replay"]["device_copy_GBps"] = 2 * buf_bytes / (timed(lambda: buf_i.copy_(buf_f.view(i32))) * 1e-3) / 1e9
     out["replay"]["device_read_GBps"] = buf_bytes / (timed(lambda: buf_f.max()) * 1e-3) / 1e9
+    # the register-only microkernel: Algorithm 1's arithmetic with nothing else in the way
+    sink = torch.zeros(1, dtype=f64, device="cuda")
+    alu_steps, alu_blocks = 20000, 256 * 8
+    prs.prs_measure_alu_ceiling(200, alu_blocks, sink)
+    alu_ms = timed(lambda: prs.prs_measure_alu_ceiling(alu_steps, alu_blocks, sink))
+    alu_rate = alu_steps * alu_blocks * 256 / (alu_ms * 1e-3)
+    out["alu_ceiling"] = {"pair_steps_per_s": alu_rate, "ops_per_s_at_4_per_step": 4 * alu_rate,
+                          "frac_of_nominal_fp64": 4 * alu_rate / PEAK_FP64_OPS,
+                          "note": "dependent steps of Algorithm 1's arithmetic on registers only, 8 blocks of 256 lanes per CU"}
+    out["pair_steps_vs_alu_ceiling"] = {k: v / alu_rate for k, v in out["pairs_per_s"].items()}
+    # the large-machine sweep (p in [1024, 65536], 64..4096 segments, m in [1 MiB, 1 GiB]): every 16th of its
+    # 10,000 configurations, completion times under both models
+    large_host = prs_inputs.large_p_sweep().take(np.arange(0, 10000, LARGE_EVERY))
+    large = prs.DeviceConfigs.from_host(large_host)
+    loff = prs.prs_pair_offsets(large, LARGE_P_MAX, LARGE_Q_MAX)
+    torch.cuda.synchronize()
+    large_pairs = int(loff[-1].item())
+    large_ms = {}
+    for m, nm in ((prs.PRS_UNI, "uni"), (prs.PRS_BI, "bi")):
+        wsb = torch.empty(prs.prs_workspace_bytes(prs.PRS_CALL_SIMULATE, m, prs.PRS_COST_F64, len(large), LARGE_P_MAX, LARGE_Q_MAX) + 256,
+                          dtype=torch.uint8, device="cuda")
+        res = {}
+        large_ms[nm] = timed(lambda: res.update(prs.simulate_completion_batch(large, m, LARGE_P_MAX, LARGE_Q_MAX, workspace=wsb)), reps=1)
+        assert int((res["cfg_status"] != 0).sum().item()) == 0
+        del wsb, res
+    out["large_machines"] = {"workload": f"configs[3]: every {LARGE_EVERY}th of the 10,000 configurations with p in [1024,65536], "
+                                         "q_req in [64,4096], m in [1 MiB,1 GiB], fp64 costs; completion times and baselines",
+                             "n_configs": len(large), "pairs_per_model": large_pairs, "ms": large_ms,
+                             "schedules_per_s": {k: len(large) / (v * 1e-3) for k, v in large_ms.items()},
+                             "pairs_per_s": {k: large_pairs / (v * 1e-3) for k, v in large_ms.items()},
+                             "note": "not part of the step or of value; one call per model, no warm-up"}
     # the best-segmentation search (Sections 5.2, 6.1) over the sweep's first 10,000 problems,
     # ten power-of-two segment counts each
     sub = prs.DeviceConfigs.from_host(host.take(np.arange(SEARCH_PROBLEMS)))
@@ -288,7 +378,7 @@ def main():
     uneq["note"] = "not part of the step or of value; m10 is the paper's experiment (61 problems, 7.3 %, 2.0 %)"
     out["unequal_segmentation"] = uneq
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(host)
+        out["cpu_baseline"] = cpu_baseline(host, large_host)
     print(json.dumps(out))
 
 

@@ -264,6 +264,34 @@ int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int3
                                const prs_unequal *out, void *workspace, size_t workspace_bytes, void *stream,
                                const prs_tuning *tuning);
 
+/*
+ * Butterfly against bi-greedy (Section 6.1, last paragraph and its figure of the parameters for which some
+ * message size lets the butterfly win).  For every machine size p[i] (device, n entries) the line is located
+ * by bisection over the ratio beta/gamma: gamma = 1, beta = the ratio, latency alpha; at a ratio the butterfly
+ * "wins" if for one of the message sizes m = 2^k, k = m_log2_first..m_log2_last, its time (Table III) is
+ * below the time of the reversed optimal broadcast -- the time bi-greedy meets, Table III -- at the best of the
+ * segment counts 1..min(q_max, m), each cut as in simulate_completion_batch.  Starting from [ratio_lo,
+ * ratio_hi] (the caller's bracket: wins at ratio_lo, not at ratio_hi), `steps` times the midpoint
+ * lo + (hi - lo)/2 replaces lo if the butterfly wins there, else hi.  ratio_below / ratio_above (device, n
+ * doubles, either may be NULL) receive the final lo and hi; cfg_status (device, may be NULL) PRS_CFG_OK, or
+ * PRS_CFG_BAD_PARAM for p < 2 (results NaN).  No workspace.
+ * Errors: PRS_EINVAL unless 0 <= alpha < 1e300, 0 < ratio_lo < ratio_hi < 1e100, 1 <= q_max <= 2^20,
+ * 0 <= m_log2_first <= m_log2_last <= 40, 0 <= steps <= 64, 0 <= n < 2^31.
+ */
+int butterfly_threshold_batch(const int32_t *p, int64_t n, double alpha, int32_t q_max,
+                              int32_t m_log2_first, int32_t m_log2_last,
+                              double ratio_lo, double ratio_hi, int32_t steps,
+                              double *ratio_below, double *ratio_above, int32_t *cfg_status, void *stream);
+
+/*
+ * Measurement helper, no result: `blocks` blocks of 256 lanes each run steps_per_lane dependent steps of the
+ * bare arithmetic of Algorithm 1 (Section 5: pick the two smallest of two sorted fronts, add tcomm, add tcomp --
+ * two comparisons, two additions) on registers only.  Timed by the caller, blocks * 256 * steps_per_lane steps
+ * per launch give the rate the chip reaches on this arithmetic with nothing else in the way: the practical
+ * ceiling next to the nominal fp64 rate.  sink: device, one double, never written in practice.
+ */
+int prs_measure_alu_ceiling(int64_t steps_per_lane, int32_t blocks, double *sink, void *stream);
+
 /* Version of the ABI, bumped on any incompatible change. */
 int prs_abi_version(void);
 

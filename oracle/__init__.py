@@ -378,3 +378,17 @@ def butterfly_wins_somewhere(p, alpha, beta, gamma, m_values, q_max) -> bool:
         if butterfly < best:
             return True
     return False
+
+
+def butterfly_threshold_bisect(p, alpha, q_max, m_log2_first, m_log2_last, lo, hi, steps):
+    """Section 6.1: bracket of the largest beta/gamma (gamma = 1) at which the butterfly beats the reversed optimal
+    broadcast for some message size 2^k, by bisection from [lo, hi] (wins at lo, not at hi): `steps` times the
+    midpoint lo + (hi - lo)/2 replaces lo if the butterfly wins there, else hi.  Returns (lo, hi)."""
+    ms = [2 ** k for k in range(m_log2_first, m_log2_last + 1)]
+    for _ in range(steps):
+        mid = lo + (hi - lo) * 0.5
+        if butterfly_wins_somewhere(p, float(alpha), mid, 1.0, ms, q_max):
+            lo = mid
+        else:
+            hi = mid
+    return lo, hi

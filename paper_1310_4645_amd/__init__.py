@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     PRS_CALL_SIMULATE, PRS_CALL_SCHEDULE, PRS_CALL_REPLAY, PRS_CALL_OFFSETS, PRS_CALL_SEARCH, PRS_CALL_UNEQUAL,
     DeviceConfigs, load_library, library_path, exported_symbols,
     prs_workspace_bytes, simulate_completion_batch, optimal_segmentation_batch, unequal_segmentation_batch, prs_pair_offsets,
-    greedy_schedule_batch, replay_reduction, replay_reduction_static, PrsError,
+    greedy_schedule_batch, replay_reduction, replay_reduction_static, butterfly_threshold_batch, prs_measure_alu_ceiling, PrsError,
 )

@@ -23,7 +23,7 @@ _LIB = None
 
 EXPORTS = ("prs_abi_version", "prs_workspace_bytes", "simulate_completion_batch", "prs_pair_offsets",
            "greedy_schedule_batch", "replay_reduction", "replay_reduction_static", "optimal_segmentation_batch",
-           "unequal_segmentation_batch")
+           "unequal_segmentation_batch", "butterfly_threshold_batch", "prs_measure_alu_ceiling")
 
 
 class PrsError(RuntimeError):
@@ -99,6 +99,11 @@ def load_library():
         lib.replay_reduction_static.restype = C.c_int
         lib.replay_reduction_static.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                 C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.butterfly_threshold_batch.restype = C.c_int
+        lib.butterfly_threshold_batch.argtypes = [C.c_void_p, C.c_int64, C.c_double, C.c_int32, C.c_int32, C.c_int32, C.c_double,
+                                                  C.c_double, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.prs_measure_alu_ceiling.restype = C.c_int
+        lib.prs_measure_alu_ceiling.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
         lib.optimal_segmentation_batch.restype = C.c_int
         lib.optimal_segmentation_batch.argtypes = [C.POINTER(_Configs), C.c_int64, C.c_int, C.c_int, C.c_int32, C.c_int32,
                                                    C.POINTER(_Best), C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
@@ -323,3 +328,26 @@ def replay_reduction_static(p: int, q: int, seg_elem_offset, src, dst, seg, inp,
                                      _stream())
     _check(rc, "replay_reduction_static")
     return out, status
+
+
+def butterfly_threshold_batch(p, alpha: float, q_max: int, m_log2_first: int, m_log2_last: int, ratio_lo: float,
+                              ratio_hi: float, steps: int):
+    """p: device int32 tensor of machine sizes.  Returns dict(ratio_below, ratio_above (float64), cfg_status (int32))
+    of device tensors: the bracket of the largest beta/gamma at which the butterfly still beats bi-greedy's time for
+    some message size 2^k, after `steps` bisection steps from [ratio_lo, ratio_hi]."""
+    import torch
+    lib = load_library()
+    n = int(p.shape[0])
+    out = {"ratio_below": torch.empty(n, dtype=torch.float64, device=p.device),
+           "ratio_above": torch.empty(n, dtype=torch.float64, device=p.device),
+           "cfg_status": torch.empty(n, dtype=torch.int32, device=p.device)}
+    rc = lib.butterfly_threshold_batch(_dp(p), n, float(alpha), int(q_max), int(m_log2_first), int(m_log2_last), float(ratio_lo),
+                                       float(ratio_hi), int(steps), _dp(out["ratio_below"]), _dp(out["ratio_above"]),
+                                       _dp(out["cfg_status"]), _stream())
+    _check(rc, "butterfly_threshold_batch")
+    return out
+
+
+def prs_measure_alu_ceiling(steps_per_lane: int, blocks: int, sink):
+    """Enqueues the register-only microkernel (blocks x 256 lanes x steps_per_lane steps of Algorithm 1's arithmetic)."""
+    _check(load_library().prs_measure_alu_ceiling(int(steps_per_lane), int(blocks), _dp(sink), _stream()), "prs_measure_alu_ceiling")

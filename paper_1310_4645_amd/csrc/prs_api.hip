@@ -602,6 +602,26 @@ int unequal_segmentation_batch(const prs_configs *cfg, int64_t n, int cost, int3
     return hipGetLastError() == hipSuccess ? PRS_OK : PRS_EDEVICE;
 }
 
+int butterfly_threshold_batch(const int32_t *p, int64_t n, double alpha, int32_t q_max, int32_t m_log2_first,
+                              int32_t m_log2_last, double ratio_lo, double ratio_hi, int32_t steps, double *ratio_below,
+                              double *ratio_above, int32_t *cfg_status, void *stream)
+{
+    if (n < 0 || n >= (INT64_C(1) << 31) || (n > 0 && !p) || q_max < 1 || q_max > (1 << 20) || m_log2_first < 0 ||
+        m_log2_last < m_log2_first || m_log2_last > 40 || steps < 0 || steps > 64)
+        return PRS_EINVAL;
+    if (!(alpha >= 0.0) || !(alpha < 1e300) || !(ratio_lo > 0.0) || !(ratio_hi > ratio_lo) || !(ratio_hi < 1e100)) return PRS_EINVAL;
+    if (n == 0) return PRS_OK;
+    ThresholdLaunch L{p, n, alpha, q_max, m_log2_first, m_log2_last, ratio_lo, ratio_hi, steps, ratio_below, ratio_above,
+                      cfg_status, static_cast<hipStream_t>(stream)};
+    return launch_threshold(L) == hipSuccess ? PRS_OK : PRS_EDEVICE;
+}
+
+int prs_measure_alu_ceiling(int64_t steps_per_lane, int32_t blocks, double *sink, void *stream)
+{
+    if (steps_per_lane < 0 || blocks < 1 || blocks > (1 << 20) || !sink) return PRS_EINVAL;
+    return launch_alu_ceiling(steps_per_lane, blocks, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? PRS_OK : PRS_EDEVICE;
+}
+
 int prs_pair_offsets(const prs_configs *cfg, int64_t n, int cost, int32_t p_max, int32_t q_max, int64_t *pair_offset,
                      void *workspace, size_t workspace_bytes, void *stream)
 {

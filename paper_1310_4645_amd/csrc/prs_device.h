@@ -78,6 +78,10 @@ __device__ __forceinline__ uint32_t comp_drop(uint32_t comp, int segments)
 }
 
 template <typename T>
+__device__ __forceinline__ Config<T> decode_values(int32_t p, int32_t q_req, int64_t m, T alpha, T beta, T gamma, int32_t p_max,
+                                                   int32_t q_max);
+
+template <typename T>
 __device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_t i, int32_t p_max, int32_t q_max)
 {
     Config<T> c;
@@ -108,12 +112,23 @@ __device__ __forceinline__ Config<T> decode_config(const ConfigArrays &a, int64_
         if (!schedule_fits<T>(c.p, c.q, c.alpha, c.beta, c.gamma, c.m)) c.status = PRS_CFG_BAD_PARAM;
         return c;
     }
-    c.p = a.p[i];
-    const int32_t q_req = a.q_req[i];
-    c.m = a.m[i];
-    c.alpha = static_cast<const T *>(a.alpha)[i];
-    c.beta = static_cast<const T *>(a.beta)[i];
-    c.gamma = static_cast<const T *>(a.gamma)[i];
+    return decode_values<T>(a.p[i], a.q_req[i], a.m[i], static_cast<const T *>(a.alpha)[i], static_cast<const T *>(a.beta)[i],
+                            static_cast<const T *>(a.gamma)[i], p_max, q_max);
+}
+
+// One configuration given by value: equi-segmentation from a segment count (Section 2) and the costs of a full and of
+// the last segment (Section 5).
+template <typename T>
+__device__ __forceinline__ Config<T> decode_values(int32_t p, int32_t q_req, int64_t m, T alpha, T beta, T gamma, int32_t p_max,
+                                                   int32_t q_max)
+{
+    Config<T> c;
+    c.comp = 0;
+    c.p = p;
+    c.m = m;
+    c.alpha = alpha;
+    c.beta = beta;
+    c.gamma = gamma;
     c.status = PRS_CFG_OK;
     c.q = 1; c.sz = 1; c.sz_last = 1;
     c.c_full = c.g_full = c.c_last = c.g_last = 0;
@@ -240,6 +255,22 @@ struct TimesOut {
     int32_t *q_eff, *cfg_status;
 };
 
+// Table III: reversed optimal broadcast (the time bi-greedy meets), (ceil(log2 p) + q - 1) rounds of a full segment
+template <typename T> __device__ __forceinline__ T revopt_time(const Config<T> &c)
+{
+    const T r = (c.alpha + c.beta * static_cast<T>(c.sz)) + c.gamma * static_cast<T>(c.sz);
+    return static_cast<T>(static_cast<int64_t>(ceil_log2(c.p)) + c.q - 1) * r;
+}
+
+// Table III: butterfly (reduce-scatter by recursive halving, gather by recursive doubling)
+template <typename T> __device__ __forceinline__ double butterfly_time(const Config<T> &c)
+{
+    const double Ld = static_cast<double>(ceil_log2(c.p)), fr = static_cast<double>(c.p - 1) / static_cast<double>(c.p);
+    const double md = static_cast<double>(c.m), al = static_cast<double>(c.alpha), be = static_cast<double>(c.beta),
+                 ga = static_cast<double>(c.gamma);
+    return ((2.0 * Ld) * al + (2.0 * fr) * (be * md)) + fr * (ga * md);
+}
+
 template <typename T>
 __device__ __forceinline__ void write_closed_forms(const TimesOut &o, int64_t i, const Config<T> &c, int model)
 {
@@ -264,11 +295,11 @@ __device__ __forceinline__ void write_closed_forms(const TimesOut &o, int64_t i,
     if (o.binary)
         static_cast<T *>(o.binary)[i] =
             static_cast<T>(model == PRS_UNI ? 2 * static_cast<int64_t>(N - 1) + 4 * (q - 1) : 2 * (N + q - 2)) * r;
-    if (o.revopt) static_cast<T *>(o.revopt)[i] = static_cast<T>(L + q - 1) * r;
+    if (o.revopt) static_cast<T *>(o.revopt)[i] = revopt_time<T>(c);
     const double Ld = static_cast<double>(L), fr = static_cast<double>(c.p - 1) / static_cast<double>(c.p);
     const double md = static_cast<double>(c.m), al = static_cast<double>(c.alpha), be = static_cast<double>(c.beta),
                  ga = static_cast<double>(c.gamma);
-    if (o.butterfly) o.butterfly[i] = ((2.0 * Ld) * al + (2.0 * fr) * (be * md)) + fr * (ga * md);
+    if (o.butterfly) o.butterfly[i] = butterfly_time<T>(c);
     if (o.lower_bound) {
         const double bw = (model == PRS_UNI && c.p > 2) ? 2.0 * (md * be) : md * be;
         o.lower_bound[i] = (Ld * al + bw) + fr * (md * ga);

@@ -105,6 +105,21 @@ constexpr size_t kReplayStaticBytes = static_cast<size_t>(8) << 20;
 size_t replay_scratch_bytes(int32_t p, int32_t q);          // what a replay touches of its scratch memory
 hipError_t replay_static_scratch(void **ptr);                // address of the current device's array
 
+struct ThresholdLaunch {
+    const int32_t *p;
+    int64_t n;
+    double alpha;
+    int32_t q_max, m_log2_first, m_log2_last;
+    double ratio_lo, ratio_hi;
+    int32_t steps;
+    double *ratio_below, *ratio_above;
+    int32_t *cfg_status;
+    hipStream_t stream;
+};
+hipError_t launch_threshold(const ThresholdLaunch &L);
+
+hipError_t launch_alu_ceiling(int64_t steps, int32_t blocks, double *sink, hipStream_t stream);
+
 struct OffsetsLaunch {
     ConfigArrays cfg;
     int64_t n;

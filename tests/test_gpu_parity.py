@@ -587,6 +587,34 @@ def test_butterfly_threshold_by_bisection(prs, p):
     assert hi_g < 5 and abs(math.sqrt(lo_g * hi_g) / O.butterfly_threshold_closed_form(p) - 1) < 0.1
 
 
+def test_butterfly_threshold_entry_point(prs):
+    """Section 6.1 on the device: the bracket of the largest beta/gamma at which the butterfly still beats
+    bi-greedy's time for some message size, bisection step for step against the oracle's (same midpoints, same
+    closed forms, so the brackets are equal bit for bit); for 4 to 1024 processors the line stays below 5, as the
+    section says, and within a tenth of its closed form; a machine of one processor is reported, not run."""
+    import torch
+    ps = [4, 8, 16, 32, 64, 100, 128, 256, 512, 1000, 1024, 1]
+    got = prs.butterfly_threshold_batch(torch.tensor(ps, dtype=torch.int32, device="cuda"), 1000.0, 512, 4, 22, 0.25, 16.0, 12)
+    _sync()
+    lo, hi, st = _np(got["ratio_below"]), _np(got["ratio_above"]), _np(got["cfg_status"])
+    assert list(st) == [0] * 11 + [1] and np.isnan(lo[11]) and np.isnan(hi[11])
+    for i in (1, 4, 5, 10):                                              # p = 8, 64, 100, 1024
+        assert (lo[i], hi[i]) == O.butterfly_threshold_bisect(ps[i], 1000.0, 512, 4, 22, 0.25, 16.0, 12), ps[i]
+    assert np.all(hi[:11] < 5) and np.all(hi[:11] - lo[:11] == (16.0 - 0.25) / 4096)
+    for i in range(2, 11):                                               # from 16 processors on the line rises with p
+        assert abs(0.5 * (lo[i] + hi[i]) / O.butterfly_threshold_closed_form(ps[i]) - 1) < 0.1, ps[i]
+    grow = [0.5 * (lo[i] + hi[i]) for i in (2, 3, 4, 6, 7, 8, 10)]
+    assert all(a < b for a, b in zip(grow, grow[1:]))
+    # no steps: the caller's bracket comes back; another latency against the oracle as well
+    same = prs.butterfly_threshold_batch(torch.tensor([64], dtype=torch.int32, device="cuda"), 10.0, 512, 4, 22, 0.25, 16.0, 0)
+    other = prs.butterfly_threshold_batch(torch.tensor([64], dtype=torch.int32, device="cuda"), 10.0, 512, 4, 22, 0.25, 16.0, 9)
+    _sync()
+    assert (_np(same["ratio_below"])[0], _np(same["ratio_above"])[0]) == (0.25, 16.0)
+    assert (_np(other["ratio_below"])[0], _np(other["ratio_above"])[0]) == O.butterfly_threshold_bisect(64, 10.0, 512, 4, 22, 0.25, 16.0, 9)
+    with pytest.raises(prs.PrsError):
+        prs.butterfly_threshold_batch(torch.tensor([64], dtype=torch.int32, device="cuda"), 10.0, 512, 4, 22, 16.0, 0.25, 3)
+
+
 # --------------------------------------------------------------------------- unequal segmentation (Section 8)
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 

@@ -627,6 +627,18 @@ def test_butterfly_can_only_win_for_small_beta_over_gamma():
     assert O.butterfly_wins_somewhere(64, 10.0, 2.0, 1.0, ms, 512) and O.butterfly_wins_somewhere(64, 1e5, 2.0, 1.0, [2 ** k for k in range(4, 30)], 4096)
 
 
+def test_butterfly_threshold_bisection_brackets_the_line():
+    """The bisection the device entry point mirrors: its bracket holds the closed form of the line to within a
+    tenth, stays below 5 for 1024 processors, and returns the caller's bracket when no step is taken."""
+    assert O.butterfly_threshold_bisect(64, 1000.0, 512, 4, 22, 0.25, 16.0, 0) == (0.25, 16.0)
+    for p in (16, 64):
+        lo, hi = O.butterfly_threshold_bisect(p, 1000.0, 512, 4, 22, 0.25, 16.0, 9)
+        assert hi - lo == (16.0 - 0.25) / 512 and hi < 5
+        assert abs(0.5 * (lo + hi) / O.butterfly_threshold_closed_form(p) - 1) < 0.1
+        ms = [2 ** k for k in range(4, 23)]
+        assert O.butterfly_wins_somewhere(p, 1000.0, lo, 1.0, ms, 512) and not O.butterfly_wins_somewhere(p, 1000.0, hi, 1.0, ms, 512)
+
+
 # --------------------------------------------------------------------------- best segmentation (Sections 5.2, 6.1)
 def _table1_pipeline_uni(p, q, m, a, b, g):
     sz = -(-m // q)
