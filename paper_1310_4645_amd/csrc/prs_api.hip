@@ -70,7 +70,7 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 //                                     classes in one launch;
 //   bi-greedy:                        1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
 //                                     q <= 1023; the general kernel for the rest and for reruns.
-enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral };
+enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral, kBiBlock };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
@@ -81,6 +81,7 @@ struct ClassSpec {
     int lpc;                  // kBiGroup: lanes per configuration
     size_t rows_per_group;    // kBiGroup: words of sent-bit rows per configuration slot
     int32_t p_cap;            // capacity of the per-processor arrays of this class
+    int32_t q_cap;            // capacity of its per-segment arrays
     bool lds;                 // state (uni batch) / small arrays and maybe the bitmap (bi general) in LDS
     size_t lds_bytes;
     int32_t lds_bitmap_bytes;
@@ -92,10 +93,29 @@ struct Layout {
     size_t header, order, retry, total;
     ClassLimits limits;
     ClassSpec cls[kClasses];
+    ClassSpec rerun;              // bi-greedy: the one-wavefront kernel for configurations the group kernel hands back
     bool bi_on[kClasses - 1];     // bi-greedy group classes a configuration can fall into
 };
 
 static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+// the one-configuration-per-wavefront bi-greedy kernel: where its arrays go for machines of up to p_cap processors
+static void general_spec(ClassSpec &c, int32_t p_cap, int32_t q_cap)
+{
+    c.kind = kBiGeneral;
+    c.p_cap = p_cap;
+    c.q_cap = q_cap;
+    c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
+    const size_t small = bi_small_bytes(p_cap, q_cap), bitmap = bi_bitmap_bytes(p_cap, q_cap);
+    if (small <= kLdsPerBlockMax / 2) {
+        c.lds = true;
+        c.lds_bitmap_bytes = static_cast<int32_t>(bitmap < kBitmapLdsMax ? bitmap : kBitmapLdsMax);
+        c.lds_bytes = small + static_cast<size_t>(c.lds_bitmap_bytes);
+    } else if (bi_masks_bytes(p_cap) <= kLdsPerBlockMax) {
+        c.lds_bytes = bi_masks_bytes(p_cap);             // bit sets in LDS, lists and counters in the slot
+    }
+    c.slot_bytes = bi_slot_bytes(p_cap, q_cap, c.lds);
+}
 
 static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t q_max, const prs_tuning *tuning = nullptr)
 {
@@ -125,6 +145,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         }
         for (int k = 0; k < kClasses; ++k) {
             ClassSpec &c = L.cls[k];
+            c.q_cap = q_max;
             c.kind = sched ? kUniSched : kUniTimes; c.lpc = 0; c.rows_per_group = 0; c.lds = true; c.lds_bitmap_bytes = 0;
             c.p_cap = (p_max + 15) / 16 * 16;                    // keeps every per-lane array 64-byte aligned
             c.lds_bytes = sched ? uni_sched_lds_bytes() : uni_times_lds_bytes();
@@ -142,6 +163,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
         ClassSpec &c = L.cls[k];
         const bool last = k == kClasses - 1;
         c.p_cap = last ? p_max : (L.limits.p[k] < p_max ? L.limits.p[k] : p_max);
+        c.q_cap = q_max;
         c.lds = false; c.lds_bytes = 0; c.lds_bitmap_bytes = 0; c.slot_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
         const bool possible = last || k == 0 || L.limits.p[k - 1] < p_max;   // can a configuration land here?
         if (!last) {
@@ -153,21 +175,20 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
             const int32_t q_cap = q_max < kGroupQMax ? q_max : kGroupQMax;
             c.rows_per_group = static_cast<size_t>(q_cap) * c.lpc;
             c.slot_bytes = c.rows_per_group * 8 * (64 / c.lpc);
+        } else if (p_max > L.limits.p[kClasses - 2] && bi_block_lds_bytes(c.p_cap) <= kLdsPerBlockMax) {
+            // thousands of processors: one block of 16 wavefronts per configuration, bit sets in LDS
+            c.kind = kBiBlock;
+            c.lds_bytes = bi_block_lds_bytes(c.p_cap);
+            c.slot_bytes = bi_block_slot_bytes(c.p_cap, q_max);
         } else {
-            // general one-configuration-per-wavefront kernel: big p or many segments, and reruns
-            c.kind = kBiGeneral;
-            const size_t small = bi_small_bytes(c.p_cap, q_max), bitmap = bi_bitmap_bytes(c.p_cap, q_max);
-            if (small <= kLdsPerBlockMax / 2) {
-                c.lds = true;
-                c.lds_bitmap_bytes = static_cast<int32_t>(bitmap < kBitmapLdsMax ? bitmap : kBitmapLdsMax);
-                c.lds_bytes = small + static_cast<size_t>(c.lds_bitmap_bytes);
-            } else if (bi_masks_bytes(c.p_cap) <= kLdsPerBlockMax) {
-                c.lds_bytes = bi_masks_bytes(c.p_cap);             // bit sets in LDS, lists and counters in the slot
-            }
-            c.slot_bytes = bi_slot_bytes(c.p_cap, q_max, c.lds);
+            // one configuration per wavefront: many segments on a small machine, or more processors than the block
+            // kernel's LDS holds
+            general_spec(c, c.p_cap, q_max);
         }
         int64_t g;
-        if (c.lds) {
+        if (c.kind == kBiBlock) {
+            g = 2 * kCUs;
+        } else if (c.lds) {
             int64_t per_cu = static_cast<int64_t>(kLdsPerCU / (c.lds_bytes < 1024 ? 1024 : c.lds_bytes));
             if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
             if (per_cu < 1) per_cu = 1;
@@ -191,6 +212,22 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     }
     for (int k = 0; k < kClasses; ++k) {
         ClassSpec &c = L.cls[k];
+        c.slot_offset = off;
+        off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
+    }
+    // reruns come from the group classes only: at most 1024 processors and 1023 segments
+    {
+        ClassSpec &c = L.rerun;
+        general_spec(c, p_max < L.limits.p[kClasses - 2] ? p_max : L.limits.p[kClasses - 2], q_max < kGroupQMax ? q_max : kGroupQMax);
+        int64_t g = kGlobalClassGrid;
+        if (c.lds) {
+            int64_t per_cu = static_cast<int64_t>(kLdsPerCU / (c.lds_bytes < 1024 ? 1024 : c.lds_bytes));
+            if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
+            if (per_cu < 1) per_cu = 1;
+            g = per_cu * kCUs;
+        }
+        if (g > n) g = n < 1 ? 1 : n;
+        c.grid = static_cast<int>(g);
         c.slot_offset = off;
         off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
     }
@@ -229,8 +266,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
     P.stream = st;
     if (launch_plan(P) != hipSuccess) return PRS_EDEVICE;
     int32_t *retry = reinterpret_cast<int32_t *>(ws + lay.retry);
-    auto general = [&](int k, const int32_t *order, int cls) {          // batch / general kernels
-        const ClassSpec &c = lay.cls[k];
+    auto general = [&](const ClassSpec &c, const int32_t *order, int cls) {          // batch / general kernels
         UniLaunch L;
         L.cfg = P.cfg;
         L.p_max = p_max; L.q_max = q_max; L.model = model; L.cost = cost;
@@ -242,11 +278,12 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         L.lds_bytes = c.lds_bytes;
         L.slots = ws + c.slot_offset;
         L.slot_bytes = c.slot_bytes;
-        L.slot_p = c.p_cap; L.slot_q = q_max;
+        L.slot_p = c.p_cap; L.slot_q = c.q_cap;
         L.grid = c.grid;
         L.stream = st;
         if (c.kind == kUniTimes) return launch_uni_times(L);
         if (c.kind == kUniSched) return launch_uni_sched(L);
+        if (c.kind == kBiBlock) return launch_bi_block(L);
         return launch_bi(L);
     };
     // the class with the longest-running configurations first; a class without configurations ends at once
@@ -285,12 +322,12 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             G.parts.rows_per_block = c0.slot_bytes / 8;
             G.stream = st;
             if (launch_bi_group(G) != hipSuccess) return PRS_EDEVICE;
-        } else if (general(k, P.order, k) != hipSuccess) {
+        } else if (general(c, P.order, k) != hipSuccess) {
             return PRS_EDEVICE;
         }
     }
     // bi-greedy configurations whose list of running groups did not fit go through the general kernel
-    if (model == PRS_BI && general(kClasses - 1, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
+    if (model == PRS_BI && general(lay.rerun, retry, kRetryClass) != hipSuccess) return PRS_EDEVICE;
     return PRS_OK;
 }
 

@@ -84,6 +84,10 @@ size_t uni_sched_lds_bytes();
 size_t uni_sched_slot_bytes(int32_t p_cap);
 hipError_t launch_uni_sched(const UniLaunch &L);
 hipError_t launch_bi(const BiLaunch &L);
+// one block of 16 wavefronts per configuration: thousands of processors
+size_t bi_block_slot_bytes(int32_t p_cap, int32_t q_cap);
+size_t bi_block_lds_bytes(int32_t p_cap);
+hipError_t launch_bi_block(const BiLaunch &L);
 
 struct ReplayLaunch {
     int32_t p, q;
