@@ -136,11 +136,12 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
     T t = 0, Tmax = 0;
     int ndone = 0, segStart = 0;
     int64_t emitted = 0;
+    bool lateOnly = false;
     const int64_t max_events = 4 * static_cast<int64_t>(p) * q + 16;
     for (int64_t ev = 0;; ++ev) {
         if (ev > max_events) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         // ---- port and computation state of every processor at time t, as bit sets (wavefront v takes words v, v+16, ...)
-        T minOld = kInf;
+        T minOld = kInf, minLate = kInf;             // next time a port frees / a processor may take in the last segment
         int cs = 0, cr = 0, cu = 0;                  // free send ports, free receive ports, processors with either
         for (int w = wave; w < W; w += kBlockWaves) {
             const int i = w * kWave + lane;
@@ -162,7 +163,7 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
             const bool lt = in && guardL && !(nsnt & kSentShort) && s > t + c.c_last;
             if (in && s > t && s < minOld) minOld = s;
             if (in && r > t && r < minOld) minOld = r;
-            if (lt) { const T v = s - c.c_last; if (v > t && v < minOld) minOld = v; }
+            if (lt) { const T v = s - c.c_last; if (v > t && v < minLate) minLate = v; }
             const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL), blt = ballot64(lt);
             if (lane == 0) {
                 sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; lateL[w] = blt;
@@ -172,10 +173,13 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
             }
         }
         minOld = block_min<T>(bs, minOld);
+        if (guardL) minLate = block_min<T>(bs, minLate);
         block_sum3(bs, cs, cr, cu);                   // also makes the bit sets visible to every thread
-        T minNew = kInf;
+        T minNew = kInf, minNewLate = kInf;
         while (segStart < q && rem[segStart] == 0) ++segStart;
-        for (int j = segStart; j < q; ++j) {
+        // At a time at which no port frees the candidates of every segment but the last have only become fewer
+        // since the event before: only the last segment is visited.
+        for (int j = (lateOnly && segStart < q - 1) ? q - 1 : segStart; j < q; ++j) {
             // no further pair can form at this t: a pair needs a free send port and a free receive port on two
             // different processors
             if (cs == 0 || cr == 0 || cu < 2) break;
@@ -302,7 +306,7 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
             if (guardL && !last && tc > t + c.c_last) {           // these senders cannot take the last segment in yet
                 for (int w = tid; w < W; w += kBlockThreads) lateL[w] |= sendSet[w];
                 const T v = tc - c.c_last;
-                if (v > t && v < minNew) minNew = v;
+                if (v > t && v < minNewLate) minNewLate = v;
             }
             cs -= l; cr -= l;
             int g0 = 0, g1 = 0;
@@ -318,7 +322,10 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
             __syncthreads();
         }
         if (ndone == q) break;
-        const T tn = minOld < minNew ? minOld : minNew;
+        T tn = minOld < minNew ? minOld : minNew;
+        const T tl = minLate < minNewLate ? minLate : minNewLate;
+        lateOnly = tl < tn;
+        if (lateOnly) tn = tl;
         if (!(tn < kInf)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         t = tn;
         __threadfence_block();

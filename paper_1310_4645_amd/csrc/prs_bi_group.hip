@@ -157,7 +157,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     int64_t ci = 0;             // configuration index
     Config<T> c;
     int W = 0;
-    T t = 0, Tmax = 0, minNew = kInf;
+    T t = 0, Tmax = 0, minNew = kInf, minNewLate = kInf;
     int ndone = 0, segStart = 0, j = 0, jhi = -1, ng = 0, status = 0;
     bool need_event = true, overflow = false, idle_visit = false;
     int64_t emitted = 0, out_base = 0, events = 0;
@@ -193,7 +193,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 W = (c.p + 63) >> 6;
                 valid = 0;
                 if (gl < W) valid = (gl == W - 1 && (c.p & 63)) ? (UINT64_C(1) << (c.p & 63)) - 1 : ~UINT64_C(0);
-                t = 0; Tmax = 0; minNew = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
+                t = 0; Tmax = 0; minNew = kInf; minNewLate = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
                 shortMask = 0; lateL = 0;
                 ragged = c.sz_last != c.sz;
                 guardL = ragged && c.g_last > 0;
@@ -226,8 +226,10 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
         // ---------------------------------------------------------------- advance time (Algorithm 2: t <- next port release)
         if (run && need_event) {
             T tn = t;
+            bool lateOnly = false;
             if (events > 0) {
                 tn = minNew;
+                T tl = minNewLate;
 #pragma unroll 4
                 for (int s = 0; s < ng; ++s) {
                     const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
@@ -236,14 +238,17 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     // senders of a full segment may receive the smaller last one from se - tcomm(last) on
                     if (guardL && !((shortMask >> s) & 1) && se > t + c.c_last) {
                         const T v = se - c.c_last;
-                        if (v > t && v < tn) tn = v;
+                        if (v > t && v < tl) tl = v;
                     }
                 }
+                // No port frees at such a time: since the last event the candidates of every segment but the last
+                // have only become fewer, so only the last segment is visited.
+                if (tl < tn) { tn = tl; lateOnly = true; }
                 if (!(tn < kInf)) status = PRS_CFG_STALLED;
             }
             if (++events > 4 * static_cast<int64_t>(c.p) * c.q + 16) status = PRS_CFG_STALLED;
             t = tn;
-            minNew = kInf;
+            minNew = kInf; minNewLate = kInf;
             // rebuild the port and computation sets from the groups still running; drop finished groups
             uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0, late = 0;
             uint32_t keptShort = 0;
@@ -288,7 +293,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             rfree = live & ~rbusy;
             compF = cF; compL = cL;
             j = segStart;
-            idle_visit = false;
+            idle_visit = lateOnly;
             need_event = false;
         }
 
@@ -418,7 +423,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         if (guardL && !last && tc > t + c.c_last) {      // these senders cannot take the last segment in yet
                             lateL |= sset;
                             const T v = tc - c.c_last;
-                            if (v > t && v < minNew) minNew = v;
+                            if (v > t && v < minNewLate) minNewLate = v;
                         }
                         remj -= l;
                         if (remj == 0) {                                  // only the root is left: done after the last arrival
