@@ -97,6 +97,9 @@ typedef struct prs_times {
  *   4 (k=1) or 16 (k=2) lanes, larger ones by 32.  Used if the three are >= 0 and non-decreasing (all zero:
  *   everything on 32 lanes -- also what a zeroed struct selects); otherwise, e.g. with -1, the built-in limits.
  * uni_wave_log2: configurations of at least 2^uni_wave_log2 pairs get a whole wavefront (1..39; else built-in).
+ * uni_wide_procs: uni-greedy completion times of machines with at least this many processors are computed by a
+ *   whole block per configuration, many pairs of a segment at once (>= 2; else built-in: never, the kernel is
+ *   slower than the segment pipeline on every workload measured).
  * bi_list_entries: most entries of the per-configuration list of running transfers in the bi-greedy kernel
  *   for p <= 1024; a configuration that needs more is rerun by the general kernel (1 .. built-in size; else
  *   built-in). */
@@ -104,6 +107,8 @@ typedef struct prs_tuning {
     int64_t uni_group_pairs[3];
     int32_t uni_wave_log2;
     int32_t bi_list_entries;
+    int32_t uni_wide_procs;
+    int32_t reserved;            /* 0 */
 } prs_tuning;
 
 /* Bytes of device scratch the given call needs for a batch of n

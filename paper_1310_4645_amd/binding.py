@@ -51,19 +51,21 @@ class _Unequal(C.Structure):
 
 
 class _Tuning(C.Structure):
-    _fields_ = [("uni_group_pairs", C.c_int64 * 3), ("uni_wave_log2", C.c_int32), ("bi_list_entries", C.c_int32)]
+    _fields_ = [("uni_group_pairs", C.c_int64 * 3), ("uni_wave_log2", C.c_int32), ("bi_list_entries", C.c_int32),
+                ("uni_wide_procs", C.c_int32), ("reserved", C.c_int32)]
 
 
 def _tuning(t):
-    """None, or a dict with any of uni_group_pairs (three limits), uni_wave_log2, bi_list_entries -> prs_tuning*."""
+    """None, or a dict with any of uni_group_pairs (three limits), uni_wave_log2, bi_list_entries, uni_wide_procs
+    -> prs_tuning*."""
     if t is None:
         return None
-    unknown = set(t) - {"uni_group_pairs", "uni_wave_log2", "bi_list_entries"}
+    unknown = set(t) - {"uni_group_pairs", "uni_wave_log2", "bi_list_entries", "uni_wide_procs"}
     if unknown:
         raise PrsError(f"unknown tuning fields {sorted(unknown)}")
     pairs = t.get("uni_group_pairs", (-1, -1, -1))
     return C.byref(_Tuning((C.c_int64 * 3)(*[int(v) for v in pairs]), int(t.get("uni_wave_log2", 0)),
-                           int(t.get("bi_list_entries", 0))))
+                           int(t.get("bi_list_entries", 0)), int(t.get("uni_wide_procs", 0)), 0))
 
 
 def library_path() -> str:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libprs.so")
-SOURCES = ["prs_api.hip", "prs_plan.hip", "prs_uni_times.hip", "prs_uni_sched.hip", "prs_bi.hip", "prs_bi_block.hip", "prs_bi_group.hip", "prs_replay.hip", "prs_threshold.hip", "prs_measure.hip"]
+SOURCES = ["prs_api.hip", "prs_plan.hip", "prs_uni_times.hip", "prs_uni_sched.hip", "prs_uni_wide.hip", "prs_bi.hip", "prs_bi_block.hip", "prs_bi_group.hip", "prs_replay.hip", "prs_threshold.hip", "prs_measure.hip"]
 # -ffp-contract=off: every product and sum of the cost model is rounded on its own.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

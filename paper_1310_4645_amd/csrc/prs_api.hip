@@ -70,11 +70,15 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 //                                     classes in one launch;
 //   bi-greedy:                        1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
 //                                     q <= 1023; the general kernel for the rest and for reruns.
-enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral, kBiBlock };
+enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral, kBiBlock, kUniWide };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
 constexpr int64_t kUniWork[kClasses - 1] = {1024, 8192, 262144};   // most pairs of a configuration run by 1, 4, 16 lanes
+// uni-greedy completion times: machines of at least this many processors would get a block per configuration.  Off: measured
+// on the large-machine sweep the segment pipeline through the lanes is 2 to 3 times faster (in steady state only a few
+// hundred values lie under the bound of a round); the kernel stays reachable through prs_tuning.
+constexpr int32_t kUniWideProcs = INT32_MAX;
 
 struct ClassSpec {
     ClassKind kind;
@@ -94,6 +98,7 @@ struct Layout {
     ClassLimits limits;
     ClassSpec cls[kClasses];
     ClassSpec rerun;              // bi-greedy: the one-wavefront kernel for configurations the group kernel hands back
+    ClassSpec wide;               // uni-greedy completion times: the block-per-configuration kernel (grid 0: not used)
     bool bi_on[kClasses - 1];     // bi-greedy group classes a configuration can fall into
 };
 
@@ -132,6 +137,8 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.limits.by_work = 0;
     for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = 0;
     L.limits.giant_log2 = kGiantLog2;
+    L.limits.wide_p = 0;
+    L.wide.grid = 0; L.wide.slot_bytes = 0; L.wide.slot_offset = 0;
     static const int group_lpc[kClasses - 1] = {1, 4, 16};
     if (model == PRS_UNI) {
         // classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one launch,
@@ -155,6 +162,23 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
             c.grid = k == 0 ? static_cast<int>(g) : 0;
             c.slot_offset = off;
             off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
+        }
+        // completion times of machines with thousands of processors: a block per configuration
+        if (!sched) {
+            int32_t wide_p = kUniWideProcs;
+            if (tuning && tuning->uni_wide_procs > 0) wide_p = tuning->uni_wide_procs;
+            if (p_max >= wide_p) L.limits.wide_p = wide_p;
+            {                                                          // its slots are always there: the size of the workspace does not depend on the tuning
+                ClassSpec &c = L.wide;
+                c.kind = kUniWide; c.p_cap = p_max; c.q_cap = q_max; c.lds = true; c.lds_bytes = uni_wide_lds_bytes();
+                c.lds_bitmap_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
+                c.slot_bytes = uni_wide_slot_bytes(p_max);
+                int64_t g = 2 * kCUs;
+                if (g > n) g = n < 1 ? 1 : n;
+                c.grid = static_cast<int>(g);
+                c.slot_offset = off;
+                off += align256(static_cast<size_t>(c.grid) * c.slot_bytes);
+            }
         }
         L.total = off;
         return L;
@@ -284,9 +308,11 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         if (c.kind == kUniTimes) return launch_uni_times(L);
         if (c.kind == kUniSched) return launch_uni_sched(L);
         if (c.kind == kBiBlock) return launch_bi_block(L);
+        if (c.kind == kUniWide) return launch_uni_wide(L);
         return launch_bi(L);
     };
     // the class with the longest-running configurations first; a class without configurations ends at once
+    if (lay.limits.wide_p > 0 && general(lay.wide, P.order, kWideClass) != hipSuccess) return PRS_EDEVICE;
     bool groups_done = false;
     for (int k = kClasses - 1; k >= 0; --k) {
         const ClassSpec &c = lay.cls[k];

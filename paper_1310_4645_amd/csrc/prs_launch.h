@@ -83,6 +83,10 @@ hipError_t launch_uni_times(const UniLaunch &L);
 size_t uni_sched_lds_bytes();
 size_t uni_sched_slot_bytes(int32_t p_cap);
 hipError_t launch_uni_sched(const UniLaunch &L);
+// uni-greedy completion times of machines with thousands of processors: one block per configuration
+size_t uni_wide_slot_bytes(int32_t p_cap);
+size_t uni_wide_lds_bytes();
+hipError_t launch_uni_wide(const UniLaunch &L);
 hipError_t launch_bi(const BiLaunch &L);
 // one block of 16 wavefronts per configuration: thousands of processors
 size_t bi_block_slot_bytes(int32_t p_cap, int32_t q_cap);

@@ -10,14 +10,16 @@ namespace prs {
 constexpr int kClasses = 4;
 constexpr int kWorkBuckets = 40;     // floor(log2(work)) buckets, heaviest first
 constexpr int kRetryClass = kClasses; // pseudo class: configurations handed back to the general kernel
+constexpr int kWideClass = kClasses;  // uni-greedy completion times: machines large enough for a block of their own
+constexpr int kPlanClasses = kClasses + 1;
 
 struct PlanHeader {
     unsigned long long ticket[kClasses + 1];
     int32_t class_begin[kClasses + 1];
     int32_t class_count[kClasses + 1];
-    int32_t hist[kClasses * kWorkBuckets];
-    int32_t start[kClasses * kWorkBuckets];
-    int32_t cursor[kClasses * kWorkBuckets];
+    int32_t hist[kPlanClasses * kWorkBuckets];
+    int32_t start[kPlanClasses * kWorkBuckets];
+    int32_t cursor[kPlanClasses * kWorkBuckets];
     // The heaviest configurations of the last class (at least 2^giant_log2 pairs) come first in its order; the
     // uni-greedy kernels run them on whole wavefronts and draw them from a ticket counter of their own.
     int32_t giant_count;
@@ -35,6 +37,7 @@ struct ClassLimits {
     int32_t by_work;
     int64_t work[kClasses - 1];
     int32_t giant_log2;          // configurations of the last class with at least 2^giant_log2 pairs are "giant"
+    int32_t wide_p;              // by_work only: machines of at least this many processors form the class kWideClass (0: none)
 };
 
 struct PlanLaunch {

@@ -13,6 +13,7 @@ __device__ __forceinline__ int plan_bucket(const ConfigArrays &cfg, int64_t i, i
     if (lim.by_work) {
         for (int k = kClasses - 2; k >= 0; --k)
             if (work <= lim.work[k]) cls = k;
+        if (lim.wide_p > 0 && c.p >= lim.wide_p && cfg.comp_m == 0) cls = kWideClass;
     } else {
         for (int k = kClasses - 2; k >= 0; --k)
             if (c.p <= lim.p[k] && c.q <= lim.q) cls = k;
@@ -27,11 +28,11 @@ __global__ void plan_clear(PlanHeader *h)
     const int i = threadIdx.x;
     if (i < kClasses + 1) { h->ticket[i] = 0ULL; h->class_begin[i] = 0; h->class_count[i] = 0; }
     if (i == 0) { h->giant_count = 0; h->ticket_giant = 0ULL; }
-    for (int k = i; k < kClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
+    for (int k = i; k < kPlanClasses * kWorkBuckets; k += blockDim.x) { h->hist[k] = 0; h->start[k] = 0; h->cursor[k] = 0; }
 }
 
 constexpr int kPlanThreads = 256;
-constexpr int kPlanBins = kClasses * kWorkBuckets;
+constexpr int kPlanBins = kPlanClasses * kWorkBuckets;
 
 // Both passes count inside the block first (LDS) and touch the global counters once per block and bin: with one
 // global atomic per configuration, a batch of millions spends its time queueing on a few dozen addresses.
@@ -50,11 +51,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_hist(ConfigArrays cfg, int6
         if (local[k] != 0) atomicAdd(&h->hist[k], local[k]);
 }
 
-__global__ void plan_scan(PlanHeader *h, int32_t giant_log2)
+// n_classes: kClasses, or kPlanClasses when the batch has a class of wide machines (otherwise that slot is the
+// retry list of bi-greedy, which starts empty at position 0 of an array of its own)
+__global__ void plan_scan(PlanHeader *h, int32_t giant_log2, int n_classes)
 {
     if (threadIdx.x != 0) return;
     int32_t run = 0;
-    for (int c = 0; c < kClasses; ++c) {
+    for (int c = 0; c < n_classes; ++c) {
         h->class_begin[c] = run;
         for (int b = 0; b < kWorkBuckets; ++b) {
             h->start[c * kWorkBuckets + b] = run;
@@ -94,11 +97,11 @@ hipError_t launch_plan(const PlanLaunch &L)
     hipLaunchKernelGGL(plan_clear, dim3(1), dim3(256), 0, L.stream, L.header);
     if (L.cost == PRS_COST_I64) {
         hipLaunchKernelGGL((plan_hist<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
-        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2, (L.limits.by_work && L.limits.wide_p > 0) ? kPlanClasses : kClasses);
         hipLaunchKernelGGL((plan_scatter<int64_t>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     } else {
         hipLaunchKernelGGL((plan_hist<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header);
-        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2);
+        hipLaunchKernelGGL(plan_scan, dim3(1), dim3(64), 0, L.stream, L.header, L.limits.giant_log2, (L.limits.by_work && L.limits.wide_p > 0) ? kPlanClasses : kClasses);
         hipLaunchKernelGGL((plan_scatter<double>), dim3(blocks), dim3(kPlanThreads), 0, L.stream, L.cfg, L.n, L.p_max, L.q_max, L.limits, L.header, L.order);
     }
     return hipGetLastError();

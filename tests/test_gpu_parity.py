@@ -159,6 +159,42 @@ def test_uni_every_group_size(prs, grouping):
     _check_schedules(prs, hostf, 0, 160, 80, tuning=tuning)
 
 
+def test_uni_times_a_block_per_configuration(prs):
+    """The kernel that gives a machine of thousands of processors a block of its own and forms many pairs of a
+    segment at once, here fed with machines of every size (the limit lowered to two processors): completion
+    times of the integer sweep, ragged integer cases, fp64 costs whose sums collide in rounding, and machines
+    of a few thousand processors, against Algorithm 1 in the oracle, bit for bit."""
+    tuning = {"uni_wide_procs": 2}
+    host = prs_inputs.tiny_sweep()
+    got = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(host), 0, 16, 8, tuning=tuning)
+    _sync()
+    _check_times(got, O.simulate_batch(host, 0), exact=True)
+    rng = np.random.default_rng(606)
+    n = 80
+    p = rng.integers(2, 300, n).astype(np.int32)
+    p[:6] = [2, 3, 63, 64, 65, 257]
+    q = rng.integers(1, 40, n).astype(np.int32)
+    m = (q.astype(np.int64) * rng.integers(1, 4, n) + rng.integers(0, 2, n)).astype(np.int64)
+    host = prs_inputs.SweepConfigs(p, q, m, rng.integers(1, 12, n).astype(np.int64), rng.integers(0, 4, n).astype(np.int64),
+                                   rng.integers(0, 4, n).astype(np.int64), "i64")
+    got = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(host), 0, 300, 40, tuning=tuning)
+    _sync()
+    _check_times(got, O.simulate_batch(host, 0), exact=True)
+    hostf = prs_inputs.SweepConfigs(p[:40], q[:40], m[:40], np.full(40, 1.0), np.full(40, 0.0), np.full(40, 2.0 ** -52), "f64")
+    gotf = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(hostf), 0, 300, 40, tuning=tuning)
+    _sync()
+    assert np.array_equal(_np(gotf["greedy"]), O.simulate_batch(hostf, 0).T_greedy)
+    # more values under the bound than a round looks at (gamma large against the spacing of the ready times)
+    pb = np.array([2500, 3000, 5000, 4097], np.int32)
+    hostb = prs_inputs.SweepConfigs(pb, np.array([6, 3, 4, 9], np.int32), np.array([12, 9, 4, 27], np.int64), np.array([1, 0, 3, 2], np.int64),
+                                    np.array([1, 1, 1, 2], np.int64), np.array([50, 7, 0, 1], np.int64), "i64")
+    gotb = prs.simulate_completion_batch(prs.DeviceConfigs.from_host(hostb), 0, 8192, 16, tuning={"uni_wide_procs": 2048})
+    _sync()
+    want = [O.uni_greedy_time(int(pb[i]), O.equi_sizes(int(hostb.m[i]), int(hostb.q_req[i])), int(hostb.alpha[i]), int(hostb.beta[i]),
+                              int(hostb.gamma[i])) for i in range(4)]
+    assert list(_np(gotb["greedy"])) == want and np.all(_np(gotb["cfg_status"]) == 0)
+
+
 # --------------------------------------------------------------------------- fp64 sweeps
 def _fast_subset(host, budget, limit):
     """indices of configurations the plain oracle finishes quickly (cost ~ p^2 q)."""
