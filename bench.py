@@ -131,6 +131,8 @@ def main():
                     help="enqueue the four sweep calls of a step, which do not depend on each other, on four streams "
                          "(default: one after the other on one stream; measured: 225 ms per step against 206, every "
                          "call already fills the GPU)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="print after the timed step and the per-call pass (profiler runs: none of the extra blocks)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of 1 GiB (calibrates the HBM byte counters of a profiler run)")
     args = ap.parse_args()
@@ -317,6 +319,9 @@ def main():
                                    "bi": n_pairs * 20.0 / (part_ms["schedule_bi"] * 1e-3) / 1e9},
         "roofline": roof,
     }
+    if args.step_only:
+        print(json.dumps(out))
+        return
     # outside the timed step: what plain device kernels reach on the same 4 GiB of buffers (the practical ceilings
     # next to the published 8 TB/s): a device-to-device copy (bytes read + bytes written) and a read-only pass
     def timed(fn, reps=3):
