@@ -174,6 +174,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
                 c.lds_bitmap_bytes = 0; c.lpc = 0; c.rows_per_group = 0;
                 c.slot_bytes = uni_wide_slot_bytes(p_max);
                 int64_t g = 2 * kCUs;
+                while (g > 1 && static_cast<size_t>(g) * c.slot_bytes > (static_cast<size_t>(1) << 30)) g /= 2;   // at most 1 GiB of the workspace
                 if (g > n) g = n < 1 ? 1 : n;
                 c.grid = static_cast<int>(g);
                 c.slot_offset = off;

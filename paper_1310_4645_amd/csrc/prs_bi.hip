@@ -127,8 +127,9 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
     for (int64_t ev = 0;; ++ev) {
         if (ev > max_events) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         // ---- port and computation state of every processor at time t, as bit sets
-        T minOld = kInf;
+        T minOld = kInf, minLate = kInf;             // next time a port frees / a processor may take in the smaller last segment
         int cs = 0, cr = 0, cu = 0;                  // free send ports, free receive ports, processors with either
+        int csAll = 0;                               // free send ports of processors with something left to send
         // (four words of processors per round: their loads are issued together, ahead of the ballots and stores)
         for (int w4 = 0; w4 < W; w4 += 4) {
             T s4[4], r4[4], c4[4];
@@ -163,17 +164,19 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                 const bool lt = in && guardL && !(nsnt & kSentShort) && s > t + c.c_last;
                 if (in && s > t && s < minOld) minOld = s;
                 if (in && r > t && r < minOld) minOld = r;
-                if (lt) { const T v = s - c.c_last; if (v > t && v < minOld) minOld = v; }
+                if (lt) { const T v = s - c.c_last; if (v > t && v < minLate) minLate = v; }
                 const uint64_t bsf = ballot64(sf), brf = ballot64(rf), bcF = ballot64(cF), bcL = ballot64(cL), blt = ballot64(lt);
                 if (lane == 0 && w < W) { sfree[w] = bsf; rfree[w] = brf; compF[w] = bcF; compL[w] = bcL; lateL[w] = blt; }
                 cs += __popcll(bsf & ~bcL);
                 cr += __popcll(brf & ~bcL);
                 cu += __popcll((bsf | brf) & ~bcL);
+                csAll += __popcll(bsf);
             }
         }
         minOld = wave_min(minOld);
+        minLate = wave_min(minLate);
         __syncthreads();
-        T minNew = kInf;
+        T minNew = kInf, minNewLate = kInf;
         while (segStart < q && rem[segStart] == 0) ++segStart;
         for (int j = segStart; j < q; ++j) {
             // no further pair can form at this t: a pair needs a free send port and a free receive port on two
@@ -292,9 +295,9 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
                 for (int w0 = 0; w0 < W; w0 += kWave)
                     if (w0 + lane < W) lateL[w0 + lane] |= sendSet[w0 + lane];
                 const T v = tc - c.c_last;
-                if (v > t && v < minNew) minNew = v;
+                if (v > t && v < minNewLate) minNewLate = v;
             }
-            cs -= l; cr -= l;
+            cs -= l; cr -= l; csAll -= l;
             cu -= wave_sum(gone);
             remj -= l;
             if (lane == 0) rem[j] = remj;
@@ -305,7 +308,11 @@ __device__ T run_bi(const Config<T> &c, const BiState &bs, const SchedOut &sched
             __syncthreads();
         }
         if (ndone == q) break;
-        const T tn = minOld < minNew ? minOld : minNew;
+        T tn = minOld < minNew ? minOld : minNew;
+        // The instants at which a sender may take in the last segment count only if a processor with something left to
+        // send has a free send port: otherwise nothing can pair before a port frees.
+        const T tl = minLate < minNewLate ? minLate : minNewLate;
+        if (csAll > 0 && tl < tn) tn = tl;
         if (!(tn < kInf)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         t = tn;
     }

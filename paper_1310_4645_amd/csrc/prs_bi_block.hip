@@ -143,6 +143,7 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
         // ---- port and computation state of every processor at time t, as bit sets (wavefront v takes words v, v+16, ...)
         T minOld = kInf, minLate = kInf;             // next time a port frees / a processor may take in the last segment
         int cs = 0, cr = 0, cu = 0;                  // free send ports, free receive ports, processors with either
+        int csAll = 0;                               // free send ports of processors with something left to send
         for (int w = wave; w < W; w += kBlockWaves) {
             const int i = w * kWave + lane;
             const bool in = i < p;
@@ -170,11 +171,13 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
                 cs += __popcll(bsf & ~bcL);
                 cr += __popcll(brf & ~bcL);
                 cu += __popcll((bsf | brf) & ~bcL);
+                csAll += __popcll(bsf);
             }
         }
         minOld = block_min<T>(bs, minOld);
         if (guardL) minLate = block_min<T>(bs, minLate);
         block_sum3(bs, cs, cr, cu);                   // also makes the bit sets visible to every thread
+        { int z0 = 0, z1 = 0; block_sum3(bs, csAll, z0, z1); }
         T minNew = kInf, minNewLate = kInf;
         while (segStart < q && rem[segStart] == 0) ++segStart;
         // At a time at which no port frees the candidates of every segment but the last have only become fewer
@@ -308,7 +311,7 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
                 const T v = tc - c.c_last;
                 if (v > t && v < minNewLate) minNewLate = v;
             }
-            cs -= l; cr -= l;
+            cs -= l; cr -= l; csAll -= l;
             int g0 = 0, g1 = 0;
             block_sum3(bs, gone, g0, g1);
             cu -= gone;
@@ -324,7 +327,8 @@ __device__ T run_bi_block(const Config<T> &c, char *lds, char *slot, const Block
         if (ndone == q) break;
         T tn = minOld < minNew ? minOld : minNew;
         const T tl = minLate < minNewLate ? minLate : minNewLate;
-        lateOnly = tl < tn;
+        // without a free send port on a processor that still has something to send nothing can pair before a port frees
+        lateOnly = csAll > 0 && tl < tn;
         if (lateOnly) tn = tl;
         if (!(tn < kInf)) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }
         t = tn;

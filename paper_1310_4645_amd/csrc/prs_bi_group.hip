@@ -242,8 +242,10 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     }
                 }
                 // No port frees at such a time: since the last event the candidates of every segment but the last
-                // have only become fewer, so only the last segment is visited.
-                if (tl < tn) { tn = tl; lateOnly = true; }
+                // have only become fewer, so only the last segment is visited -- and if no processor with something
+                // left to send has a free send port, nothing can pair before the next port frees: the time is skipped.
+                const bool anySender = group_sum<LPC>(sfree != 0 ? 1 : 0) != 0;
+                if (anySender && tl < tn) { tn = tl; lateOnly = true; }
                 if (!(tn < kInf)) status = PRS_CFG_STALLED;
             }
             if (++events > 4 * static_cast<int64_t>(c.p) * c.q + 16) status = PRS_CFG_STALLED;

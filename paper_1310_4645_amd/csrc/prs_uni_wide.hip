@@ -38,7 +38,7 @@ template <typename T> __device__ __forceinline__ int merge_rank(const T *X, int 
 }
 
 template <typename T>
-__device__ T run_uni_wide(const Config<T> &c, char *lds, T *bufA, T *bufOut, T *bufB)
+__device__ T run_uni_wide(const Config<T> &c, char *lds, T *bufA, T *bufOut, T *bufB, int32_t *status)
 {
     const int tid = static_cast<int>(threadIdx.x), lane = lane_id(), wave = tid >> 6;
     T *tA = reinterpret_cast<T *>(lds), *tB = tA + kWideTile;
@@ -75,6 +75,7 @@ __device__ T run_uni_wide(const Config<T> &c, char *lds, T *bufA, T *bufOut, T *
 #pragma unroll
             for (int w = 0; w < kWideWaves; ++w) { cntA += part[w]; cntB += part[kWideWaves + w]; }
             const int np = (cntA + cntB) >> 1;          // at least one: the two smallest are under the limit
+            if (np == 0) { *status = PRS_CFG_STALLED; return CostTraits<T>::bad(); }   // (never with finite times; ends the loop for all threads alike)
             if (tid < np) {
                 const int kk = 2 * tid + 1;              // the later value of pair tid starts it
                 const int ia = merge_rank<T>(tA, cntA, tB, cntB, kk), ib = kk - ia;
@@ -119,13 +120,14 @@ __global__ __launch_bounds__(kWideThreads) void uni_wide_kernel(ConfigArrays cfg
         const int64_t i = order[begin + ticket];
         const Config<T> c = decode_config<T>(cfg, i, p_max, q_max);
         T result = CostTraits<T>::bad();
-        if (c.status == PRS_CFG_OK)
+        int32_t status = c.status;
+        if (status == PRS_CFG_OK)
             result = run_uni_wide<T>(c, lds_raw, reinterpret_cast<T *>(slot), reinterpret_cast<T *>(slot + third),
-                                     reinterpret_cast<T *>(slot + 2 * third));
+                                     reinterpret_cast<T *>(slot + 2 * third), &status);
         if (tid == 0) {
             write_closed_forms<T>(times, i, c, model);
-            if (times.cfg_status) times.cfg_status[i] = c.status;
-            if (times.greedy) static_cast<T *>(times.greedy)[i] = result;
+            if (times.cfg_status) times.cfg_status[i] = status;
+            if (times.greedy) static_cast<T *>(times.greedy)[i] = status == PRS_CFG_OK ? result : CostTraits<T>::bad();
         }
     }
 }
