@@ -383,27 +383,30 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         if (!(tc > t)) status = PRS_CFG_STALLED;
                         if (kSched) {                                     // e-th sender pairs with e-th receiver
                             // segment and start time are the same for all pairs of the visit: the lanes of the
-                            // group write them side by side
-                            for (int e = gl; e < l; e += LPC) {
+                            // group write them side by side, four pairs each
+                            for (int e = 4 * gl; e < l; e += 4 * LPC) {
                                 const int64_t o = out_base + emitted + e;
-                                if (sched.seg) sched.seg[o] = j;
-                                if (sched.tstart) static_cast<T *>(sched.tstart)[o] = t;
+                                if (e + 4 <= l) {
+                                    const int32_t j4[4] = {j, j, j, j};
+                                    const T t4[4] = {t, t, t, t};
+                                    if (sched.seg) __builtin_memcpy(sched.seg + o, j4, sizeof(j4));
+                                    if (sched.tstart) __builtin_memcpy(static_cast<T *>(sched.tstart) + o, t4, sizeof(t4));
+                                } else {
+                                    for (int i = 0; e + i < l; ++i) {
+                                        if (sched.seg) sched.seg[o + i] = j;
+                                        if (sched.tstart) static_cast<T *>(sched.tstart)[o + i] = t;
+                                    }
+                                }
                             }
-                            uint64_t m = sset;
-                            int e = exS;
-                            while (m) {
-                                const int b = __builtin_ctzll(m);
-                                m &= m - 1;
-                                if (sched.src) sched.src[out_base + emitted + e] = gl * 64 + b;
-                                ++e;
+                            if (sched.src) {
+                                int32_t *const o = sched.src + (out_base + emitted + exS);
+                                const int n = emit_set_bits(o, static_cast<uint32_t>(sset), gl * 64);
+                                emit_set_bits(o + n, static_cast<uint32_t>(sset >> 32), gl * 64 + 32);
                             }
-                            m = rset;
-                            e = exR;
-                            while (m) {
-                                const int b = __builtin_ctzll(m);
-                                m &= m - 1;
-                                if (sched.dst) sched.dst[out_base + emitted + e] = gl * 64 + b;
-                                ++e;
+                            if (sched.dst) {
+                                int32_t *const o = sched.dst + (out_base + emitted + exR);
+                                const int n = emit_set_bits(o, static_cast<uint32_t>(rset), gl * 64);
+                                emit_set_bits(o + n, static_cast<uint32_t>(rset >> 32), gl * 64 + 32);
                             }
                         }
                         emitted += l;

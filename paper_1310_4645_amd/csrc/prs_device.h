@@ -173,6 +173,22 @@ template <> __device__ __forceinline__ double wrap_add<double>(double a, double 
 #define PRS_KEEP_BRANCH() asm volatile("" ::: "memory")
 #endif
 
+// Writes base + b for every set bit b of w, in rising order, to out[0], out[1], ...; returns how many.  Four at a
+// time while four are left: a 16-byte store costs the memory pipeline what a 4-byte store does.
+__device__ __forceinline__ int emit_set_bits(int32_t *out, uint32_t w, int base)
+{
+    int n = 0;
+    while (__builtin_popcount(w) >= 4) {
+        int32_t v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[i] = base + __builtin_ctz(w); w &= w - 1; }
+        __builtin_memcpy(out + n, v, sizeof(v));
+        n += 4;
+    }
+    while (w) { out[n++] = base + __builtin_ctz(w); w &= w - 1; }
+    return n;
+}
+
 // ---------------------------------------------------------------- wavefront primitives
 __device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & (kWave - 1); }
 
