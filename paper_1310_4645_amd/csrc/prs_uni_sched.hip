@@ -36,6 +36,51 @@ template <typename T> __device__ __forceinline__ bool key_less(T xa, int32_t ia,
     return xa < xb || (xa == xb && ia < ib);
 }
 
+// Entries [lo, n) of a per-lane array of processor indices are sorted; the new index wi belongs among them.  Moves
+// the larger ones up by one place and returns the place that is now free for wi.  Entry i sits in LDS at
+// ring[((ringBase + i) & (kRingS - 1)) * kWave + lane] as long as n + 1 - i <= kRingS (the new entry takes over the
+// slot of the one kRingS places back) and in the workspace at buf[i] once i < rows_done; both copies are kept right.
+// Four entries are read from LDS at a time: the reads are independent of each other, so a move of up to four places
+// costs one LDS round trip.
+__device__ __forceinline__ int make_room(int32_t *ring, int32_t *buf, int ringBase, int n, int lo, int rows_done, int32_t wi,
+                                         int lane)
+{
+    constexpr int M = kRingS - 1;
+    int at = n;
+    for (;;) {
+        int32_t m[4];
+        bool up[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m[i] = ring[((ringBase + at - 1 - i) & M) * kWave + lane];
+        bool more = true;
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            more = more && at - 1 - i >= lo && n + 2 - (at - i) <= kRingS && m[i] > wi;
+            up[i] = more;
+            c += more ? 1 : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (up[i]) {
+                ring[((ringBase + at - i) & M) * kWave + lane] = m[i];
+                if (at - i < rows_done) buf[at - i] = m[i];
+            }
+        }
+        at -= c;
+        if (c < 4) break;
+    }
+    // entries too old for LDS, one at a time from the workspace
+    while (at > lo && n + 2 - at > kRingS) {
+        const int32_t mv = buf[at - 1];
+        if (!(mv > wi)) break;
+        if (n + 1 - at <= kRingS) ring[((ringBase + at) & M) * kWave + lane] = mv;
+        if (at < rows_done) buf[at] = mv;
+        --at;
+    }
+    return at;
+}
+
 template <typename T, int G>
 __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays &cfg, int32_t p_max, int32_t q_max,
                                                const SchedOut &sched, PlanHeader *plan, const int32_t *order, int cls, int part,
@@ -200,20 +245,12 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             // The new entry takes over the LDS slot of the one kRingS places back, so an insertion that
             // reaches that far reads the workspace copy.
             auto put = [&](T wx, int32_t wi, int run_from) {
-                const int rows_done = fW;
                 int at = w;
-                const bool in_order = !(lastWi > wi);                         // the usual case: nothing to move, nothing to read
-                for (;;) {
-                    if (at <= run_from || in_order) break;
-                    const int32_t mv = w + 2 - at <= kRingS ? ringI[((segBase + at - 1) & M) * kWave + lane] : myI[at - 1];
-                    if (!(mv > wi)) break;
-                    if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = mv;
-                    if (at < rows_done) myI[at] = mv;
-                    --at;
-                }
+                // the usual case: the index is larger than the last one written, nothing to move, nothing to read
+                if (lastWi > wi && w > run_from) at = make_room(ringI, myI, segBase, w, run_from, fW, wi, lane);
                 ringX[(wtot & M) * kWave + lane] = wx;
                 if (w + 1 - at <= kRingS) ringI[((segBase + at) & M) * kWave + lane] = wi;
-                if (at < rows_done) myI[at] = wi;
+                if (at < fW) myI[at] = wi;
                 if (at == w) lastWi = wi;                                     // index of the last entry written
                 ++w; ++wtot;
             };
@@ -233,21 +270,12 @@ __device__ __forceinline__ void uni_sched_body(char *lds_raw, const ConfigArrays
             if (ns == 0 || !(tr == lastBx)) brun = ns;
             lastBx = tr;
             {
-                const int rows_done = fB;
                 int at = ns;
                 const int ib = bpos - segBase;
                 const int lo = brun > ib ? brun : ib;
-                const bool in_order = !(lastBi > rcv);
-                for (;;) {
-                    if (at <= lo || in_order) break;
-                    const int32_t mv = ns + 2 - at <= kRingS ? ringB[((segBase + at - 1) & M) * kWave + lane] : bufB[at - 1];
-                    if (!(mv > rcv)) break;
-                    if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = mv;
-                    if (at < rows_done) bufB[at] = mv;
-                    --at;
-                }
+                if (lastBi > rcv && ns > lo) at = make_room(ringB, bufB, segBase, ns, lo, fB, rcv, lane);
                 if (ns + 1 - at <= kRingS) ringB[((segBase + at) & M) * kWave + lane] = rcv;
-                if (at < rows_done) bufB[at] = rcv;
+                if (at < fB) bufB[at] = rcv;
                 if (at == ns) lastBi = rcv;                                   // receiver of the last B entry
             }
             // ---- consume
