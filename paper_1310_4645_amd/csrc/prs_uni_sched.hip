@@ -70,13 +70,30 @@ __device__ __forceinline__ int make_room(int32_t *ring, int32_t *buf, int ringBa
         at -= c;
         if (c < 4) break;
     }
-    // entries too old for LDS, one at a time from the workspace
+    // entries too old for LDS come from the workspace, eight loads in flight at a time (two runs of equal values
+    // that each span hundreds of processors are merged this way, entry by entry of the later one)
     while (at > lo && n + 2 - at > kRingS) {
-        const int32_t mv = buf[at - 1];
-        if (!(mv > wi)) break;
-        if (n + 1 - at <= kRingS) ring[((ringBase + at) & M) * kWave + lane] = mv;
-        if (at < rows_done) buf[at] = mv;
-        --at;
+        int32_t m[8];
+        bool up[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m[i] = buf[at - 1 - i > 0 ? at - 1 - i : 0];
+        bool more = true;
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            more = more && at - 1 - i >= lo && m[i] > wi;
+            up[i] = more;
+            c += more ? 1 : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (up[i]) {
+                if (n + 1 - (at - i) <= kRingS) ring[((ringBase + at - i) & M) * kWave + lane] = m[i];
+                if (at - i < rows_done) buf[at - i] = m[i];
+            }
+        }
+        at -= c;
+        if (c < 8) break;
     }
     return at;
 }
