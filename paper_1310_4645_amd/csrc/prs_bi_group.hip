@@ -157,7 +157,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     int64_t ci = 0;             // configuration index
     Config<T> c;
     int W = 0;
-    T t = 0, Tmax = 0, minNew = kInf, minNewLate = kInf;
+    T t = 0, Tmax = 0, minNew = kInf, minNewLate = kInf, minOld = kInf, minOldLate = kInf;
     int ndone = 0, segStart = 0, j = 0, jhi = -1, ng = 0, status = 0;
     bool need_event = true, overflow = false, idle_visit = false;
     int64_t emitted = 0, out_base = 0, events = 0;
@@ -193,7 +193,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 W = (c.p + 63) >> 6;
                 valid = 0;
                 if (gl < W) valid = (gl == W - 1 && (c.p & 63)) ? (UINT64_C(1) << (c.p & 63)) - 1 : ~UINT64_C(0);
-                t = 0; Tmax = 0; minNew = kInf; minNewLate = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
+                t = 0; Tmax = 0; minNew = kInf; minNewLate = kInf; minOld = kInf; minOldLate = kInf; ndone = 0; segStart = 0; j = 0; jhi = -1; ng = 0; cur = 0;
                 shortMask = 0; lateL = 0;
                 ragged = c.sz_last != c.sz;
                 guardL = ragged && c.g_last > 0;
@@ -228,19 +228,11 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             T tn = t;
             bool lateOnly = false;
             if (events > 0) {
-                tn = minNew;
-                T tl = minNewLate;
-#pragma unroll 4
-                for (int s = 0; s < ng; ++s) {
-                    const T se = gS[(cur * kCap + s) * kGroups + gw], re = gR[(cur * kCap + s) * kGroups + gw];
-                    if (se > t && se < tn) tn = se;
-                    if (re > t && re < tn) tn = re;
-                    // senders of a full segment may receive the smaller last one from se - tcomm(last) on
-                    if (guardL && !((shortMask >> s) & 1) && se > t + c.c_last) {
-                        const T v = se - c.c_last;
-                        if (v > t && v < tl) tl = v;
-                    }
-                }
+                // the earliest end of a send or a combine after t, and the earliest time from which the sender of a
+                // full segment may take in the smaller last one (end of its send - tcomm(last)): of the transfers begun
+                // since the last event (kept up by the visits) and of the older ones (found when the sets were rebuilt)
+                tn = minNew < minOld ? minNew : minOld;
+                const T tl = minNewLate < minOldLate ? minNewLate : minOldLate;
                 // No port frees at such a time: since the last event the candidates of every segment but the last
                 // have only become fewer, so only the last segment is visited -- and if no processor with something
                 // left to send has a free send port, nothing can pair before the next port frees: the time is skipped.
@@ -250,7 +242,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
             }
             if (++events > 4 * static_cast<int64_t>(c.p) * c.q + 16) status = PRS_CFG_STALLED;
             t = tn;
-            minNew = kInf; minNewLate = kInf;
+            minNew = kInf; minNewLate = kInf; minOld = kInf; minOldLate = kInf;
             // rebuild the port and computation sets from the groups still running; drop finished groups
             uint64_t sbusy = 0, rbusy = 0, cF = 0, cL = 0, late = 0;
             uint32_t keptShort = 0;
@@ -273,7 +265,13 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                     if (busy || (pend && (shortEntry || !ragged || t + c.c_last > se))) cL |= rm;
                     // Section 2 the other way round: the combine of the smaller last segment, received now, would
                     // begin while the sender of a full segment is still sending
-                    if (guardL && !shortEntry && se > t + c.c_last) late |= sm;
+                    if (guardL && !shortEntry && se > t + c.c_last) {
+                        late |= sm;
+                        const T v = se - c.c_last;
+                        if (v > t && v < minOldLate) minOldLate = v;
+                    }
+                    if (se > t && se < minOld) minOld = se;               // the next event among the transfers that go on
+                    if (re > t && re < minOld) minOld = re;
                     gS[(nxt * kCap + keep) * kGroups + gw] = se;          // same value from every lane of the group
                     gR[(nxt * kCap + keep) * kGroups + gw] = re;
                     if (keep != s) { gSm[keep * kWave + lane] = sm; gRm[keep * kWave + lane] = rm; }

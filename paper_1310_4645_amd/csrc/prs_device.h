@@ -244,15 +244,23 @@ __device__ __forceinline__ int64_t next_ticket(unsigned long long *counter)
 // keep the k lowest set bits of mask (k <= 0: none, k >= popcount: all)
 __device__ __forceinline__ uint64_t lowest_bits(uint64_t mask, int k)
 {
-    if (k <= 0) return 0;
-    if (k >= __popcll(mask)) return mask;
-    int pos = 0;                       // after the loop: index of the k-th set bit
+    // without branches, on the 32-bit half that holds the k-th set bit
+    const uint32_t lo = static_cast<uint32_t>(mask), hi = static_cast<uint32_t>(mask >> 32);
+    const int plo = __builtin_popcount(lo), phi = __builtin_popcount(hi);
+    const bool in_lo = k <= plo;
+    const uint32_t w = in_lo ? lo : hi;
+    int kk = in_lo ? k : k - plo;
+    uint32_t pos = 0;                  // after the loop: index of the kk-th set bit of w
 #pragma unroll
-    for (int w = 32; w > 0; w >>= 1) {
-        const int cnt = __popcll((mask >> pos) & ((UINT64_C(1) << w) - 1));
-        if (cnt < k) { pos += w; k -= cnt; }
+    for (uint32_t width = 16; width > 0; width >>= 1) {
+        const int cnt = __builtin_popcount((w >> pos) & ((1u << width) - 1));
+        const bool up = cnt < kk;
+        pos += up ? width : 0;
+        kk -= up ? cnt : 0;
     }
-    return mask & ((UINT64_C(2) << pos) - 1);
+    const uint32_t part = w & ((2u << pos) - 1);
+    const uint64_t some = in_lo ? static_cast<uint64_t>(part) : (static_cast<uint64_t>(part) << 32) | lo;
+    return k <= 0 ? 0 : (k >= plo + phi ? mask : some);
 }
 
 __device__ __forceinline__ uint64_t highest_bits(uint64_t mask, int k)
