@@ -244,9 +244,12 @@ __device__ __forceinline__ int64_t next_ticket(unsigned long long *counter)
 // keep the k lowest set bits of mask (k <= 0: none, k >= popcount: all)
 __device__ __forceinline__ uint64_t lowest_bits(uint64_t mask, int k)
 {
-    // without branches, on the 32-bit half that holds the k-th set bit
+    // all of them or none: the usual case for all but one word of a set, and a wavefront of such words skips the search
     const uint32_t lo = static_cast<uint32_t>(mask), hi = static_cast<uint32_t>(mask >> 32);
     const int plo = __builtin_popcount(lo), phi = __builtin_popcount(hi);
+    if (k <= 0) return 0;
+    if (k >= plo + phi) return mask;
+    // on the 32-bit half that holds the k-th set bit
     const bool in_lo = k <= plo;
     const uint32_t w = in_lo ? lo : hi;
     int kk = in_lo ? k : k - plo;
@@ -260,7 +263,7 @@ __device__ __forceinline__ uint64_t lowest_bits(uint64_t mask, int k)
     }
     const uint32_t part = w & ((2u << pos) - 1);
     const uint64_t some = in_lo ? static_cast<uint64_t>(part) : (static_cast<uint64_t>(part) << 32) | lo;
-    return k <= 0 ? 0 : (k >= plo + phi ? mask : some);
+    return some;
 }
 
 __device__ __forceinline__ uint64_t highest_bits(uint64_t mask, int k)
