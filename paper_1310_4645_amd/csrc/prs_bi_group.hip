@@ -81,43 +81,7 @@ template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, in
     return 0;
 }
 
-template <int LPC> __device__ __forceinline__ int group_min(int v)
-{
-    if (LPC == 4) {
-        int u = dpp_move<kQuadXor1>(v); v = u < v ? u : v;
-        u = dpp_move<kQuadXor2>(v); v = u < v ? u : v;
-    } else if (LPC == 16) {
-        int u = dpp_move<kRowRor + 8>(v); v = u < v ? u : v;
-        u = dpp_move<kRowRor + 4>(v); v = u < v ? u : v;
-        u = dpp_move<kRowRor + 2>(v); v = u < v ? u : v;
-        u = dpp_move<kRowRor + 1>(v); v = u < v ? u : v;
-    }
-    return v;
-}
-
 constexpr int kNoSegment = 1 << 20;
-
-// Smallest value of a bit-sliced counter over the processors in `set` (kNoSegment if the set is empty):
-// walk the planes from the top, keeping the members whose bit can still be 0.
-__device__ __forceinline__ int sliced_min(const uint64_t (&plane)[kPlanes], uint64_t set)
-{
-    if (set == 0) return kNoSegment;
-    int v = 0;
-#pragma unroll
-    for (int b = kPlanes - 1; b >= 0; --b) {
-        const uint64_t zero = set & ~plane[b];
-        if (zero) set = zero; else v |= 1 << b;
-    }
-    return v;
-}
-
-// processors of `set` whose bit-sliced counter equals v
-__device__ __forceinline__ uint64_t sliced_equal(const uint64_t (&plane)[kPlanes], uint64_t set, int v)
-{
-#pragma unroll
-    for (int b = 0; b < kPlanes; ++b) set &= ((v >> b) & 1) ? plane[b] : ~plane[b];
-    return set;
-}
 
 __device__ __forceinline__ void sliced_increment(uint64_t (&plane)[kPlanes], uint64_t who)
 {
@@ -166,9 +130,8 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     uint32_t shortMask = 0;     // bit s: list entry s carries the smaller last segment
     bool ragged = false, guardL = false;   // the last segment is smaller; and its combine takes time
     uint64_t cnt[kPlanes];      // bit-sliced: segments sent per processor
-    uint64_t nxt_seg[kPlanes];  // bit-sliced: a segment index below which the processor has sent everything
 #pragma unroll
-    for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
+    for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
     c.p = 2; c.q = 1; c.status = 0; c.c_full = c.c_last = c.g_full = c.g_last = 0;
 
     for (;;) {
@@ -199,7 +162,7 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 guardL = ragged && c.g_last > 0;
                 need_event = true; overflow = false; idle_visit = false; emitted = 0; events = 0;
 #pragma unroll
-                for (int b = 0; b < kPlanes; ++b) { cnt[b] = 0; nxt_seg[b] = 0; }
+                for (int b = 0; b < kPlanes; ++b) cnt[b] = 0;
             }
         }
         // wavefront-wide exit: every group out of tickets and idle
@@ -301,29 +264,22 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
         const bool visit = run && !need_event && status == PRS_CFG_OK;
         if (visit) {
             // A pair for segment j needs a processor with a free send port and a different one with a free
-            // receive port that both still hold j and are not excluded by a computation.  nxt_seg bounds
-            // from below the first segment a processor still holds (the root holds every unfinished one),
-            // so segments below the larger of the two smallest bounds are skipped.  If a visit paired
+            // receive port that both still hold j and are not excluded by a computation.  If a visit paired
             // nobody although every candidate still held the segment, no later segment can pair either:
             // its candidates are a subset.  Exclusion by a pending computation depends on tcomm(j),
             // shorter for the last segment only: segments before the last use the full-length exclusion
-            // set, the last one its own.
+            // set, the last one its own.  (A per-processor lower bound of the first segment still held, kept
+            // as a bit-sliced counter, let a visit jump over segments its candidates had all sent; keeping it
+            // up cost more than the visits it saved.)
             {
-                const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
                 int jn = kNoSegment;
                 if (!idle_visit) {
                     const uint64_t as = sfree & ~compF, ar = rfree & ~compF;
-                    int v1 = sliced_min(nxt_seg, as);
-                    int v2 = sliced_min(nxt_seg, ar & ~rootbit);
-                    if (ar & rootbit) v2 = v2 < segStart ? v2 : segStart;
                     int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
-                    v1 = group_min<LPC>(v1); v2 = group_min<LPC>(v2);
                     ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
                     nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
                     const bool pairable = ns1 > 0 && nr1 > 0 && !(ns1 == 1 && nr1 == 1 && nb1 == 1);
-                    int cand = v1 > v2 ? v1 : v2;
-                    if (cand < j) cand = j;
-                    if (pairable && cand < c.q - 1) jn = cand;
+                    if (pairable && j < c.q - 1) jn = j;
                 }
                 if (jn == kNoSegment && j <= c.q - 1) {               // only the last segment is left to try
                     const uint64_t as = sfree & ~compL, ar = rfree & ~compL & ~lateL;
@@ -343,8 +299,6 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 if (j <= jhi && gl < W) row = myrows[static_cast<size_t>(j) * LPC + gl];
                 const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
                 const uint64_t memb = ~row & valid;                       // still hold segment j (root: until done)
-                // a processor whose bound points at j but has sent j already: the bound moves up
-                sliced_increment(nxt_seg, sliced_equal(nxt_seg, row & valid, j));
                 int remj = group_sum<LPC>(__popcll(memb & ~rootbit));
                 if (remj == 0) {                                          // everybody has sent segment j
                     if (j == segStart) ++segStart;
@@ -412,7 +366,6 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         sfree &= ~sset;
                         rfree &= ~rset;
                         sliced_increment(cnt, sset);                     // one more sent segment for the senders
-                        sliced_increment(nxt_seg, sliced_equal(nxt_seg, sset, j));
                         if (ng < list_entries) {
                             gS[(cur * kCap + ng) * kGroups + gw] = tc; gR[(cur * kCap + ng) * kGroups + gw] = tr;
                             gSm[ng * kWave + lane] = sset; gRm[ng * kWave + lane] = rset;
