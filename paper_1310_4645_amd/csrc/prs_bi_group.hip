@@ -83,6 +83,15 @@ template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, in
 
 constexpr int kNoSegment = 1 << 20;
 
+// How many processors of the group are in `a`, in `b` and in both, each counted up to two per word (enough to tell
+// whether two different processors are there): the three counts travel in one sum.
+template <int LPC> __device__ __forceinline__ void few_of_each(uint64_t a, uint64_t b, int &na, int &nb, int &nboth)
+{
+    const int ca = __popcll(a), cb = __popcll(b), cc = __popcll(a & b);
+    const int packed = group_sum<LPC>((ca > 2 ? 2 : ca) | ((cb > 2 ? 2 : cb) << 8) | ((cc > 2 ? 2 : cc) << 16));
+    na = packed & 255; nb = (packed >> 8) & 255; nboth = packed >> 16;
+}
+
 __device__ __forceinline__ void sliced_increment(uint64_t (&plane)[kPlanes], uint64_t who)
 {
 #pragma unroll
@@ -275,17 +284,15 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 int jn = kNoSegment;
                 if (!idle_visit) {
                     const uint64_t as = sfree & ~compF, ar = rfree & ~compF;
-                    int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
-                    ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
-                    nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
+                    int ns1, nr1, nb1;
+                    few_of_each<LPC>(as, ar, ns1, nr1, nb1);
                     const bool pairable = ns1 > 0 && nr1 > 0 && !(ns1 == 1 && nr1 == 1 && nb1 == 1);
                     if (pairable && j < c.q - 1) jn = j;
                 }
                 if (jn == kNoSegment && j <= c.q - 1) {               // only the last segment is left to try
                     const uint64_t as = sfree & ~compL, ar = rfree & ~compL & ~lateL;
-                    int ns1 = __popcll(as), nr1 = __popcll(ar), nb1 = __popcll(as & ar);
-                    ns1 = group_sum<LPC>(ns1 > 2 ? 2 : ns1); nr1 = group_sum<LPC>(nr1 > 2 ? 2 : nr1);
-                    nb1 = group_sum<LPC>(nb1 > 2 ? 2 : nb1);
+                    int ns1, nr1, nb1;
+                    few_of_each<LPC>(as, ar, ns1, nr1, nb1);
                     if (ns1 > 0 && nr1 > 0 && !(ns1 == 1 && nr1 == 1 && nb1 == 1)) jn = c.q - 1;
                 }
                 j = jn == kNoSegment ? c.q : jn;
@@ -299,16 +306,20 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                 if (j <= jhi && gl < W) row = myrows[static_cast<size_t>(j) * LPC + gl];
                 const uint64_t rootbit = gl == 0 ? UINT64_C(1) : 0;
                 const uint64_t memb = ~row & valid;                       // still hold segment j (root: until done)
-                int remj = group_sum<LPC>(__popcll(memb & ~rootbit));
+                const uint64_t comp = last ? compL : compF;
+                const uint64_t sOK = memb & ~comp & sfree, rOK = memb & ~comp & rfree & ~(last ? lateL : UINT64_C(0));
+                const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
+                const int pf = __popcll(fr);
+                // counts of up to 1024 processors travel two to a sum
+                const int memb_free = group_sum<LPC>(__popcll(memb & ~rootbit) | (pf << 16));
+                int remj = memb_free & 0xFFFF;
+                const int nf_ = memb_free >> 16;
                 if (remj == 0) {                                          // everybody has sent segment j
                     if (j == segStart) ++segStart;
                     ++j;
                 } else {
-                    const uint64_t comp = last ? compL : compF;
-                    const uint64_t sOK = memb & ~comp & sfree, rOK = memb & ~comp & rfree & ~(last ? lateL : UINT64_C(0));
-                    const uint64_t fr = sOK & rOK, so = sOK ^ fr, ro = rOK ^ fr;
-                    const int pf = __popcll(fr);
-                    const int ns_ = group_sum<LPC>(__popcll(so)), nr_ = group_sum<LPC>(__popcll(ro)), nf_ = group_sum<LPC>(pf);
+                    const int send_recv = group_sum<LPC>(__popcll(so) | (__popcll(ro) << 16));
+                    const int ns_ = send_recv & 0xFFFF, nr_ = send_recv >> 16;
                     int toSendLast, toRecvFirst;                          // free processors go to the shorter list
                     if (ns_ == nr_) {
                         toSendLast = toRecvFirst = nf_ / 2;
@@ -326,8 +337,8 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
                         const uint64_t frR = lowest_bits(fr, toRecvFirst - exF);
                         const uint64_t frS = highest_bits(fr, exF + pf - (nf_ - toSendLast));
                         uint64_t sset = so | frS, rset = ro | frR;
-                        const int exS = group_exclusive_scan<LPC>(__popcll(sset), gl);
-                        const int exR = group_exclusive_scan<LPC>(__popcll(rset), gl);
+                        const int exSR = group_exclusive_scan<LPC>(__popcll(sset) | (__popcll(rset) << 16), gl);
+                        const int exS = exSR & 0xFFFF, exR = exSR >> 16;
                         sset = lowest_bits(sset, l - exS);                // first l entries of each list
                         rset = lowest_bits(rset, l - exR);
                         const T cj = last ? c.c_last : c.c_full, gj = last ? c.g_last : c.g_full;
