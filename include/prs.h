@@ -94,7 +94,7 @@ typedef struct prs_times {
  * configurations are spread over the lanes of a wavefront, never a result; tests use it to push one batch
  * through every code path.
  * uni_group_pairs[k]: a uni-greedy configuration of at most this many send/receive pairs is run by 1 (k=0),
- *   4 (k=1) or 16 (k=2) lanes, larger ones by 32.  Used if the three are >= 0 and non-decreasing (all zero:
+ *   4 (k=1; 8 where schedules are written) or 16 (k=2) lanes, larger ones by 32.  Used if the three are >= 0 and non-decreasing (all zero:
  *   everything on 32 lanes -- also what a zeroed struct selects); otherwise, e.g. with -1, the built-in limits.
  * uni_wave_log2: configurations of at least 2^uni_wave_log2 pairs get a whole wavefront (1..39; else built-in).
  * uni_wide_procs: uni-greedy completion times of machines with at least this many processors are computed by a

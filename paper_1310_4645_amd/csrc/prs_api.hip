@@ -66,7 +66,7 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 // ---- size classes and workspace layout (shared by prs_workspace_bytes and the launches) --------------
 //
 // A batch is split into four classes, each run by the kernel and the LDS allocation that fit it:
-//   uni-greedy (times and schedules): by number of pairs; 1, 4, 16 or 32 lanes per configuration, all four
+//   uni-greedy (times and schedules): by number of pairs; 1, 4 (schedules: 8), 16 or 32 lanes per configuration, all four
 //                                     classes in one launch;
 //   bi-greedy:                        1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
 //                                     q <= 1023; the general kernel for the rest and for reruns.
@@ -74,7 +74,8 @@ enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral, kBiBlock, kUniWide 
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
-constexpr int64_t kUniWork[kClasses - 1] = {1024, 8192, 262144};   // most pairs of a configuration run by 1, 4, 16 lanes
+constexpr int64_t kUniWork[kClasses - 1] = {1024, 8192, 262144};        // completion times: most pairs of a configuration run by 1, 4, 16 lanes
+constexpr int64_t kUniWorkSched[kClasses - 1] = {1024, 65536, 262144};  // schedules: by 1, 8, 16 lanes (measured best on the sweep)
 // uni-greedy completion times: machines of at least this many processors would get a block per configuration.  Off: measured
 // on the large-machine sweep the segment pipeline through the lanes is 2 to 3 times faster (in steady state only a few
 // hundred values lie under the bound of a round); the kernel stays reachable through prs_tuning.
@@ -141,10 +142,10 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.wide.grid = 0; L.wide.slot_bytes = 0; L.wide.slot_offset = 0;
     static const int group_lpc[kClasses - 1] = {1, 4, 16};
     if (model == PRS_UNI) {
-        // classes by number of pairs (1, 4, 16 or 32 lanes per configuration), all run by one launch,
+        // classes by number of pairs (1, 4 or 8, 16 or 32 lanes per configuration), all run by one launch,
         // described by class 0
         L.limits.by_work = 1;
-        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = kUniWork[k];
+        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = sched ? kUniWorkSched[k] : kUniWork[k];
         if (tuning) {                                              // never changes a result, only who runs what
             const int64_t a = tuning->uni_group_pairs[0], b = tuning->uni_group_pairs[1], c3 = tuning->uni_group_pairs[2];
             if (a >= 0 && b >= a && c3 >= b) { L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3; }

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kWave) void uni_sched_kernel(ConfigArrays cfg, int3
     __syncthreads();
     uni_sched_body<T, 16>(lds_raw, cfg, p_max, q_max, sched, plan, order, 2, kWholeClass, slot, slot_p);
     __syncthreads();
-    uni_sched_body<T, 4>(lds_raw, cfg, p_max, q_max, sched, plan, order, 1, kWholeClass, slot, slot_p);
+    uni_sched_body<T, 8>(lds_raw, cfg, p_max, q_max, sched, plan, order, 1, kWholeClass, slot, slot_p);
     __syncthreads();
     uni_sched_body<T, 1>(lds_raw, cfg, p_max, q_max, sched, plan, order, 0, kWholeClass, slot, slot_p);
 }

@@ -122,13 +122,13 @@ def test_integer_costs_ragged_segments_and_larger_p(prs, model):
 
 
 _BIG = 1000000000
-# pair-count limits of the 1-, 4- and 16-lane groups, and the binary logarithm of the pair count from which a
+# pair-count limits of the 1-, 4- (schedules: 8-) and 16-lane groups, and the binary logarithm of the pair count from which a
 # configuration gets all 64 lanes: every group size in turn gets the whole batch
 _GROUPINGS = {"64 lanes": {"uni_group_pairs": (0, 0, 0), "uni_wave_log2": 1},
               "64 and 32 lanes": {"uni_group_pairs": (0, 0, 0), "uni_wave_log2": 10},
               "32 lanes": {"uni_group_pairs": (0, 0, 0)},
               "16 lanes": {"uni_group_pairs": (0, 0, _BIG)},
-              "4 lanes": {"uni_group_pairs": (0, _BIG, _BIG)},
+              "4 or 8 lanes": {"uni_group_pairs": (0, _BIG, _BIG)},
               "1 lane": {"uni_group_pairs": (_BIG, _BIG, _BIG)}}
 
 
@@ -655,7 +655,7 @@ def test_butterfly_threshold_entry_point(prs):
 _SUMMARY = ("T_best", "cuts_best", "n_best", "T_equi", "cuts_equi", "equi_optimal")
 
 
-@pytest.mark.parametrize("grouping", [None, "64 lanes", "32 lanes", "16 lanes", "4 lanes"])
+@pytest.mark.parametrize("grouping", [None, "64 lanes", "32 lanes", "16 lanes", "4 or 8 lanes"])
 @pytest.mark.parametrize("cost", ["i64", "f64"])
 def test_unequal_segmentation_matches_the_oracle(prs, cost, grouping):
     """Every segmentation of short messages of mixed length through uni-greedy, at every group size: all
