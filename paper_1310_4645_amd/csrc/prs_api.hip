@@ -68,14 +68,15 @@ hipError_t launch_offsets(const OffsetsLaunch &L)
 // A batch is split into four classes, each run by the kernel and the LDS allocation that fit it:
 //   uni-greedy (times and schedules): by number of pairs; 1, 4 (schedules: 8), 16 or 32 lanes per configuration, all four
 //                                     classes in one launch;
-//   bi-greedy:                        1, 4 or 16 lanes per configuration for p <= 64 / 256 / 1024 and
+//   bi-greedy:                        1, 2, 4, 8 or 16 lanes per configuration for p <= 64 / 128 / 256 / 512 / 1024 and
 //                                     q <= 1023; the general kernel for the rest and for reruns.
 enum ClassKind { kUniTimes, kUniSched, kBiGroup, kBiGeneral, kBiBlock, kUniWide };
 constexpr size_t kLdsPerCU = 160 * 1024, kLdsPerBlockMax = 64 * 1024, kBitmapLdsMax = 24 * 1024;
 constexpr int kCUs = 256, kMaxBlocksPerCU = 24, kGlobalClassGrid = 1024;
 constexpr int32_t kGroupQMax = 1023;   // the several-per-wavefront bi-greedy kernel counts sent segments in 10 bit planes
-constexpr int64_t kUniWork[kClasses - 1] = {1024, 8192, 262144};        // completion times: most pairs of a configuration run by 1, 4, 16 lanes
-constexpr int64_t kUniWorkSched[kClasses - 1] = {1024, 65536, 262144};  // schedules: by 1, 8, 16 lanes (measured best on the sweep)
+constexpr int kUniGroupSizes = 3;        // group sizes below the largest; the classes between them and the last stay empty
+constexpr int64_t kUniWork[kUniGroupSizes] = {1024, 8192, 262144};        // completion times: most pairs of a configuration run by 1, 4, 16 lanes
+constexpr int64_t kUniWorkSched[kUniGroupSizes] = {1024, 65536, 262144};  // schedules: by 1, 8, 16 lanes (measured best on the sweep)
 // uni-greedy completion times: machines of at least this many processors would get a block per configuration.  Off: measured
 // on the large-machine sweep the segment pipeline through the lanes is 2 to 3 times faster (in steady state only a few
 // hundred values lie under the bound of a round); the kernel stays reachable through prs_tuning.
@@ -132,7 +133,7 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.retry = L.order + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     size_t off = L.retry + align256(static_cast<size_t>(n < 1 ? 1 : n) * 4);
     // which configurations go where
-    const int32_t plim[kClasses - 1] = {64, 256, 1024};
+    const int32_t plim[kClasses - 1] = {64, 128, 256, 512, 1024};
     for (int k = 0; k < kClasses - 1; ++k) L.limits.p[k] = plim[k];
     L.limits.q = kGroupQMax;
     L.limits.by_work = 0;
@@ -140,15 +141,21 @@ static Layout make_layout(int call, int model, int64_t n, int32_t p_max, int32_t
     L.limits.giant_log2 = kGiantLog2;
     L.limits.wide_p = 0;
     L.wide.grid = 0; L.wide.slot_bytes = 0; L.wide.slot_offset = 0;
-    static const int group_lpc[kClasses - 1] = {1, 4, 16};
+    static const int group_lpc[kClasses - 1] = {1, 2, 4, 8, 16};
     if (model == PRS_UNI) {
         // classes by number of pairs (1, 4 or 8, 16 or 32 lanes per configuration), all run by one launch,
         // described by class 0
         L.limits.by_work = 1;
-        for (int k = 0; k < kClasses - 1; ++k) L.limits.work[k] = sched ? kUniWorkSched[k] : kUniWork[k];
+        for (int k = 0; k < kClasses - 1; ++k) {
+            const int g = k < kUniGroupSizes ? k : kUniGroupSizes - 1;
+            L.limits.work[k] = sched ? kUniWorkSched[g] : kUniWork[g];
+        }
         if (tuning) {                                              // never changes a result, only who runs what
             const int64_t a = tuning->uni_group_pairs[0], b = tuning->uni_group_pairs[1], c3 = tuning->uni_group_pairs[2];
-            if (a >= 0 && b >= a && c3 >= b) { L.limits.work[0] = a; L.limits.work[1] = b; L.limits.work[2] = c3; }
+            if (a >= 0 && b >= a && c3 >= b) {
+                L.limits.work[0] = a; L.limits.work[1] = b;
+                for (int k = 2; k < kClasses - 1; ++k) L.limits.work[k] = c3;
+            }
             if (tuning->uni_wave_log2 > 0 && tuning->uni_wave_log2 < kWorkBuckets) L.limits.giant_log2 = tuning->uni_wave_log2;
         }
         for (int k = 0; k < kClasses; ++k) {
@@ -320,7 +327,7 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
         const ClassSpec &c = lay.cls[k];
         if (c.grid == 0) continue;                       // no configuration can fall in this class
         if (c.kind == kBiGroup) {
-            if (groups_done) continue;                   // the three group sizes share one launch
+            if (groups_done) continue;                   // the group sizes share one launch
             groups_done = true;
             BiGroupLaunch G;
             G.cfg = P.cfg; G.p_max = p_max; G.q_max = q_max; G.model = model; G.cost = cost;
@@ -331,20 +338,20 @@ static int run_greedy(int call, const prs_configs *cfg, int64_t n, int model, in
             // classes the blocks start with
             const ClassSpec &c0 = lay.cls[0];
             int total = c0.grid, enabled = 0;
-            static const int share[3] = {1, 2, 7};                         // tenths of the blocks that start with class 0, 1, 2
-            for (int g = 0; g < 3; ++g) {
+            static const int share[kBiGroupSizes] = {2, 2, 3, 6, 7};      // twentieths of the blocks that start with class 0 .. 4 (measured; flat around these)
+            for (int g = 0; g < kBiGroupSizes; ++g) {
                 G.parts.on[g] = lay.cls[g].kind == kBiGroup && lay.cls[g].lpc > 0 && lay.cls[g].rows_per_group > 0 && lay.bi_on[g];
                 G.parts.rows_per_group[g] = lay.cls[g].rows_per_group;
-                const int cap = bi_group_list_capacity(g == 0 ? 1 : (g == 1 ? 4 : 16));
+                const int cap = bi_group_list_capacity(lay.cls[g].lpc > 0 ? lay.cls[g].lpc : 1);
                 G.parts.list_entries[g] = (tuning && tuning->bi_list_entries > 0 && tuning->bi_list_entries < cap) ? tuning->bi_list_entries : cap;
                 if (G.parts.on[g]) enabled += share[g];
             }
             int given = 0;
-            for (int g = 2; g >= 0; --g) {
+            for (int g = kBiGroupSizes - 1; g >= 0; --g) {
                 G.parts.start[g] = G.parts.on[g] ? total * share[g] / enabled : 0;
                 given += G.parts.start[g];
             }
-            for (int g = 2; g >= 0; --g)
+            for (int g = kBiGroupSizes - 1; g >= 0; --g)
                 if (G.parts.on[g]) { G.parts.start[g] += total - given; break; }   // rounding remainder
             G.parts.rows = reinterpret_cast<uint64_t *>(ws + c0.slot_offset);
             G.parts.rows_per_block = c0.slot_bytes / 8;

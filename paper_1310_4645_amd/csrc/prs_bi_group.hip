@@ -1,7 +1,7 @@
 // Bi-greedy schedules (Lowery & Langou, Algorithm 2, Section 6.2) for p <= 1024 on gfx950:
 // several configurations per wavefront.
 //
-// A configuration is run by LPC adjacent lanes (1, 4 or 16), lane w of the group owning processors
+// A configuration is run by LPC adjacent lanes (1, 2, 4, 8 or 16), lane w of the group owning processors
 // 64w .. 64w+63 as one machine word; a wavefront carries 64/LPC configurations at once.  Nothing is kept
 // per processor:
 //  - every send/receive pair scheduled in one visit (time t, segment j) has the same end of send
@@ -25,7 +25,10 @@ constexpr int kPlanes = 10;            // bit planes of the sent-segments counte
 
 // Entries of the list of running groups per configuration.  A configuration that needs more is handed
 // to the one-configuration kernel; a launch may lower the limit (never the LDS layout) to force that path.
-__host__ __device__ constexpr int bi_group_capacity(int lpc) { return lpc == 1 ? 16 : (lpc == 4 ? 22 : 28); }
+__host__ __device__ constexpr int bi_group_capacity(int lpc)
+{
+    return lpc == 1 ? 16 : (lpc == 2 ? 16 : (lpc == 4 ? 22 : (lpc == 8 ? 26 : 28)));
+}
 int bi_group_list_capacity(int lpc) { return bi_group_capacity(lpc); }
 
 // LDS per wavefront: `cap` list entries, each with the two set words of every lane and the two times of
@@ -36,23 +39,31 @@ size_t bi_group_lds_bytes(int lpc)
     return static_cast<size_t>(bi_group_capacity(lpc)) * (64 * 16 + (64 / lpc) * 16 * (lpc == 1 ? 1 : 2));
 }
 
-// Sums, minima and prefix sums over the 4 or 16 lanes of a group use data-parallel-primitive moves (a lane
-// reads its source operand from another lane of its row of 16: quad_perm inside a quad, row_ror/row_shr inside
-// the row) instead of LDS permutes: a group is a quad or a whole row, and these reductions sit on the dependent
-// path of every visit, a dozen of them.
+// Sums and prefix sums over the lanes of a group use data-parallel-primitive moves (a lane reads its source
+// operand from another lane of its row of 16: quad_perm inside a quad, row_half_mirror between the two quads of
+// half a row, row_ror/row_shr inside the row) instead of LDS permutes: a group is a pair of lanes, a quad, half a
+// row or a whole row, and these reductions sit on the dependent path of every visit.
 template <int CTRL> __device__ __forceinline__ int dpp_move(int v)
 {
     return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);        // lanes without a source read 0
 }
 constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E;                          // quad_perm:[1,0,3,2], [2,3,0,1]
 constexpr int kQuadLane0 = 0x00, kQuadLane1 = 0x55, kQuadLane2 = 0xAA;     // quad_perm broadcasts of lane 0, 1, 2
+constexpr int kQuadEven = 0xA0;                                             // quad_perm:[0,0,2,2]: the even lane of each pair
+constexpr int kRowHalfMirror = 0x141;                                       // lane i of half a row reads lane 7 - i
 constexpr int kRowRor = 0x120, kRowShr = 0x110;                            // + distance 1..15
 
 template <int LPC> __device__ __forceinline__ int group_sum(int v)
 {
-    if (LPC == 4) {
+    if (LPC == 2) {
+        v += dpp_move<kQuadXor1>(v);
+    } else if (LPC == 4) {
         v += dpp_move<kQuadXor1>(v);
         v += dpp_move<kQuadXor2>(v);
+    } else if (LPC == 8) {
+        v += dpp_move<kQuadXor1>(v);
+        v += dpp_move<kQuadXor2>(v);
+        v += dpp_move<kRowHalfMirror>(v);                       // every lane holds its quad's sum: add the other quad's
     } else if (LPC == 16) {
         v += dpp_move<kRowRor + 8>(v);
         v += dpp_move<kRowRor + 4>(v);
@@ -65,9 +76,22 @@ template <int LPC> __device__ __forceinline__ int group_sum(int v)
 // exclusive prefix sum over the LPC lanes of a group
 template <int LPC> __device__ __forceinline__ int group_exclusive_scan(int v, int gl)
 {
-    if (LPC == 4) {
+    if (LPC == 2) {
+        const int even = dpp_move<kQuadEven>(v);
+        return gl == 0 ? 0 : even;
+    }
+    if (LPC == 4 || LPC == 8) {
         const int a0 = dpp_move<kQuadLane0>(v), a1 = dpp_move<kQuadLane1>(v), a2 = dpp_move<kQuadLane2>(v);
-        return gl == 0 ? 0 : (gl == 1 ? a0 : (gl == 2 ? a0 + a1 : a0 + a1 + a2));
+        const int gq = gl & 3;
+        int ex = gq == 0 ? 0 : (gq == 1 ? a0 : (gq == 2 ? a0 + a1 : a0 + a1 + a2));
+        if (LPC == 8) {
+            int quad = v;
+            quad += dpp_move<kQuadXor1>(quad);
+            quad += dpp_move<kQuadXor2>(quad);
+            const int other = dpp_move<kRowHalfMirror>(quad);   // the sum of the other quad of the group
+            if (gl & 4) ex += other;
+        }
+        return ex;
     }
     if (LPC == 16) {
         int inc = v;
@@ -414,10 +438,10 @@ __device__ __forceinline__ void bi_group_body(char *lds_raw, int block, const Co
     }
 }
 
-// One launch runs all three group sizes on one resident set of blocks.  The first start[2] blocks begin with
-// the 16-lane configurations, the next start[1] with the 4-lane ones, the rest with the 1-lane ones, so the
-// longest-running configurations of every class start at once; a block whose class has run out of tickets
-// goes on with the others (largest groups first).
+// One launch runs all group sizes on one resident set of blocks.  The first start[4] blocks begin with the 16-lane
+// configurations, the next start[3] with the 8-lane ones and so on, so the longest-running configurations of
+// every class start at once; a block whose class has run out of tickets goes on with the others (largest
+// groups first).
 template <typename T, bool kSched>
 __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32_t p_max, int32_t q_max, int model,
                                                          TimesOut times, SchedOut sched, PlanHeader *plan,
@@ -426,24 +450,41 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
     PRS_DYNAMIC_LDS(lds_raw);
     const int b = static_cast<int>(blockIdx.x);
     uint64_t *rows = parts.rows + static_cast<size_t>(b) * parts.rows_per_block;
-    const int first = b < parts.start[2] ? 2 : (b < parts.start[2] + parts.start[1] ? 1 : 0);
-    for (int turn = 0; turn < 3; ++turn) {
+    int first = 0, upto = 0;
+    for (int g = kBiGroupSizes - 1; g >= 0; --g) {
+        upto += parts.start[g];
+        if (b < upto) { first = g; break; }
+    }
+    for (int turn = 0; turn < kBiGroupSizes; ++turn) {
         // turn 0: the class this block starts with; then the remaining classes, largest groups first
         int cls = first;
         if (turn > 0) {
-            const int a = first == 2 ? 1 : 2, c = first == 0 ? 1 : 0;
-            cls = turn == 1 ? a : c;
+            cls = kBiGroupSizes - turn;                      // 4, 3, 2, 1 ...
+            if (cls <= first) --cls;                         // ... without the one done in turn 0
         }
         if (!parts.on[cls]) continue;
-        if (cls == 2)
-            bi_group_body<T, kSched, 16>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, rows,
-                                         parts.rows_per_group[2], parts.list_entries[2]);
-        else if (cls == 1)
-            bi_group_body<T, kSched, 4>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 1, retry, rows,
+        switch (cls) {
+        case 4:
+            bi_group_body<T, kSched, 16>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 4, retry, rows,
+                                         parts.rows_per_group[4], parts.list_entries[4]);
+            break;
+        case 3:
+            bi_group_body<T, kSched, 8>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 3, retry, rows,
+                                        parts.rows_per_group[3], parts.list_entries[3]);
+            break;
+        case 2:
+            bi_group_body<T, kSched, 4>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 2, retry, rows,
+                                        parts.rows_per_group[2], parts.list_entries[2]);
+            break;
+        case 1:
+            bi_group_body<T, kSched, 2>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 1, retry, rows,
                                         parts.rows_per_group[1], parts.list_entries[1]);
-        else
+            break;
+        default:
             bi_group_body<T, kSched, 1>(lds_raw, 0, cfg, p_max, q_max, model, times, sched, plan, order, 0, retry, rows,
                                         parts.rows_per_group[0], parts.list_entries[0]);
+            break;
+        }
         __syncthreads();
     }
 }
@@ -451,16 +492,20 @@ __global__ __launch_bounds__(kWave) void bi_group_kernel(ConfigArrays cfg, int32
 template <typename T, bool kSched> static void launch_fused(const BiGroupLaunch &L)
 {
     size_t lds = 0;
-    for (int k = 0; k < 3; ++k)
-        if (L.parts.on[k] && bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16)) > lds) lds = bi_group_lds_bytes(k == 0 ? 1 : (k == 1 ? 4 : 16));
-    const int grid = L.parts.start[0] + L.parts.start[1] + L.parts.start[2];
+    int grid = 0;
+    for (int k = 0; k < kBiGroupSizes; ++k) {
+        if (L.parts.on[k] && bi_group_lds_bytes(1 << k) > lds) lds = bi_group_lds_bytes(1 << k);
+        grid += L.parts.start[k];
+    }
     hipLaunchKernelGGL((bi_group_kernel<T, kSched>), dim3(grid), dim3(kWave), lds, L.stream, L.cfg, L.p_max, L.q_max, L.model,
                        L.times, L.sched, L.plan, L.order, L.retry, L.parts);
 }
 
 hipError_t launch_bi_group(const BiGroupLaunch &L)
 {
-    if (L.parts.start[0] + L.parts.start[1] + L.parts.start[2] == 0) return hipSuccess;
+    int blocks = 0;
+    for (int k = 0; k < kBiGroupSizes; ++k) blocks += L.parts.start[k];
+    if (blocks == 0) return hipSuccess;
     if (L.cost == PRS_COST_I64) { if (L.want_schedule) launch_fused<int64_t, true>(L); else launch_fused<int64_t, false>(L); }
     else { if (L.want_schedule) launch_fused<double, true>(L); else launch_fused<double, false>(L); }
     return hipGetLastError();

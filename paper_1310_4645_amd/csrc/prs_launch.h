@@ -48,17 +48,18 @@ size_t bi_small_bytes(int32_t p_cap, int32_t q_cap);               // masks, lis
 size_t bi_bitmap_bytes(int32_t p_cap, int32_t q_cap);              // sent bitmap
 size_t bi_masks_bytes(int32_t p_cap);                              // the bit sets and list positions among the small arrays
 size_t bi_slot_bytes(int32_t p_cap, int32_t q_cap, bool small_in_lds);   // what a bi-greedy block keeps in global memory
-// Several configurations per wavefront (p <= 1024, q <= 1023): 1, 4 or 16 lanes per configuration
+// Several configurations per wavefront (p <= 1024, q <= 1023): 1, 2, 4, 8 or 16 lanes per configuration
 // (plan classes 0, 1, 2), all three in one launch of one resident set of blocks.  start[k] blocks begin with
 // class k (so the longest-running configurations of every class start at once); every block then goes on
 // with the other classes until all tickets are gone.
+constexpr int kBiGroupSizes = kClasses - 1;   // 1, 2, 4, 8, 16 lanes per configuration
 struct BiGroupParts {
-    int start[3];
-    bool on[3];
+    int start[kBiGroupSizes];
+    bool on[kBiGroupSizes];
     uint64_t *rows;               // sent-bit rows: one slot of rows_per_block words per block
     size_t rows_per_block;
-    size_t rows_per_group[3];
-    int list_entries[3];          // entries of the list of running transfers a configuration may use (<= the LDS layout's)
+    size_t rows_per_group[kBiGroupSizes];
+    int list_entries[kBiGroupSizes];          // entries of the list of running transfers a configuration may use (<= the LDS layout's)
 };
 struct BiGroupLaunch {
     ConfigArrays cfg;

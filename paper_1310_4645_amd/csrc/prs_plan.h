@@ -7,7 +7,7 @@
 
 namespace prs {
 
-constexpr int kClasses = 4;
+constexpr int kClasses = 6;          // bi-greedy: five group sizes and the general kernel; uni-greedy uses 0, 1, 2 and the last
 constexpr int kWorkBuckets = 40;     // floor(log2(work)) buckets, heaviest first
 constexpr int kRetryClass = kClasses; // pseudo class: configurations handed back to the general kernel
 constexpr int kWideClass = kClasses;  // uni-greedy completion times: machines large enough for a block of their own

@@ -401,9 +401,9 @@ __global__ __launch_bounds__(kWave) void uni_sched_kernel(ConfigArrays cfg, int3
 {
     PRS_DYNAMIC_LDS(lds_raw);
     char *slot = slots + static_cast<size_t>(blockIdx.x) * slot_bytes;
-    uni_sched_body<T, 64>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, kGiantPart, slot, slot_p);
+    uni_sched_body<T, 64>(lds_raw, cfg, p_max, q_max, sched, plan, order, kClasses - 1, kGiantPart, slot, slot_p);
     __syncthreads();
-    uni_sched_body<T, 32>(lds_raw, cfg, p_max, q_max, sched, plan, order, 3, kRestPart, slot, slot_p);
+    uni_sched_body<T, 32>(lds_raw, cfg, p_max, q_max, sched, plan, order, kClasses - 1, kRestPart, slot, slot_p);
     __syncthreads();
     uni_sched_body<T, 16>(lds_raw, cfg, p_max, q_max, sched, plan, order, 2, kWholeClass, slot, slot_p);
     __syncthreads();

@@ -231,9 +231,9 @@ __global__ __launch_bounds__(kWave) void uni_times_kernel(ConfigArrays cfg, int3
     T *ring = reinterpret_cast<T *>(lds_raw);                    // [kRing][64]
     T *slot = reinterpret_cast<T *>(slots + static_cast<size_t>(blockIdx.x) * slot_bytes);
     // configurations of millions of pairs trail their predecessor segment by thousands of entries: a whole wavefront each
-    uni_times_body<T, 64, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, kGiantPart, slot, slot_p);
+    uni_times_body<T, 64, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, kClasses - 1, kGiantPart, slot, slot_p);
     __syncthreads();
-    uni_times_body<T, 32, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 3, kRestPart, slot, slot_p);
+    uni_times_body<T, 32, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, kClasses - 1, kRestPart, slot, slot_p);
     __syncthreads();
     uni_times_body<T, 16, kComp>(ring, cfg, p_max, q_max, model, times, plan, order, 2, kWholeClass, slot, slot_p);
     __syncthreads();
