@@ -293,7 +293,7 @@ def test_bi_configurations_handed_over_to_the_general_kernel(prs, entries):
     rng = np.random.default_rng(31 + entries)
     n = 90
     p = rng.integers(2, 400, n).astype(np.int32)
-    p[:6] = [2, 3, 64, 65, 256, 257]
+    p[:8] = [2, 3, 64, 65, 128, 129, 256, 257]                        # first and last machine of a group size
     q = rng.integers(1, 30, n).astype(np.int32)
     m = (q.astype(np.int64) * rng.integers(1, 5, n) - rng.integers(0, 2, n)).clip(1)
     host = prs_inputs.SweepConfigs(p, q, m, rng.integers(0, 12, n).astype(np.int64), rng.integers(1, 4, n).astype(np.int64),
