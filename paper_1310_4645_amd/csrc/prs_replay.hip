@@ -258,7 +258,9 @@ __device__ __forceinline__ Acc<E, VEC> load_elems(const E *ptr, int nvalid)
 {
     Acc<E, VEC> a;
     if (VEC * sizeof(E) == 16 && nvalid == VEC) {
-        const float4 f = *reinterpret_cast<const float4 *>(ptr);
+        // every input element is read once: a streaming load, which leaves the caches to the tree programs
+        typedef float row16 __attribute__((ext_vector_type(4)));
+        const row16 f = __builtin_nontemporal_load(reinterpret_cast<const row16 *>(ptr));
         const E *fe = reinterpret_cast<const E *>(&f);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) a.v[i] = fe[i];
