@@ -115,19 +115,45 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
     int32_t *base = kLds ? reinterpret_cast<int32_t *>(lds_raw) : tmp + static_cast<size_t>(k) * 8 * p;
     int32_t *parent = base, *ord = base + p, *ci = base + 2 * p, *nchild = base + 3 * p, *size = base + 4 * p,
             *offStart = base + 5 * p, *fchild = base + 6 * p, *start = base + 7 * p;
-    __shared__ int s_bad, s_count;
-    if (tid == 0) { s_bad = 0; s_count = 0; }
+    __shared__ int s_bad, s_count, s_deep;
+    if (tid == 0) { s_bad = 0; s_count = 0; s_deep = 0; }
     for (int i = tid; i < p; i += kBuildThreads) { parent[i] = -1; ord[i] = -1; nchild[i] = 0; size[i] = 1; fchild[i] = -1; }
     __syncthreads();
     // 1. who sends to whom, and when (position in emission order)
-    for (int64_t e = tid; e < n_pairs; e += kBuildThreads) {
-        if (seg[e] != k) { if (seg[e] < 0 || seg[e] >= q) s_bad = 1; continue; }
-        const int32_t s = src[e], d = dst[e];
-        if (s <= 0 || s >= p || d < 0 || d >= p || s == d) { s_bad = 1; continue; }
-        if (atomicCAS(&parent[s], -1, d) != -1) { s_bad = 1; continue; }      // sends the segment twice
-        ord[s] = static_cast<int32_t>(e);
-        atomicAdd(&nchild[d], 1);
-        atomicAdd(&s_count, 1);
+    //    A schedule written segment by segment has the p - 1 pairs of segment k in a row, at k (p - 1): if all of
+    //    those carry this block's segment (and the schedule has q (p - 1) pairs, so that every block can find its
+    //    own there and none is left over), only they are read.  Otherwise the block reads the segment index of
+    //    every pair and keeps its own, eight loads in flight per thread.
+    int64_t scan_from = 0, scan_to = n_pairs;
+    if (n_pairs == static_cast<int64_t>(q) * (p - 1)) {
+        const int64_t lo = static_cast<int64_t>(k) * (p - 1);
+        for (int64_t e = lo + tid; e < lo + p - 1; e += kBuildThreads)
+            if (seg[e] == k) atomicAdd(&s_deep, 1);
+        __syncthreads();
+        if (s_deep == p - 1) { scan_from = lo; scan_to = lo + p - 1; }
+        __syncthreads();
+        if (tid == 0) s_deep = 0;
+        __syncthreads();
+    }
+    constexpr int kAhead = 8;
+    for (int64_t e0 = scan_from + tid; e0 < scan_to; e0 += static_cast<int64_t>(kBuildThreads) * kAhead) {
+        int32_t sg[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t e = e0 + static_cast<int64_t>(u) * kBuildThreads;
+            sg[u] = e < scan_to ? seg[e] : k + 1;                              // past the end: some other segment
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t e = e0 + static_cast<int64_t>(u) * kBuildThreads;
+            if (sg[u] != k) { if (e < scan_to && (sg[u] < 0 || sg[u] >= q)) s_bad = 1; continue; }
+            const int32_t s = src[e], d = dst[e];
+            if (s <= 0 || s >= p || d < 0 || d >= p || s == d) { s_bad = 1; continue; }
+            if (atomicCAS(&parent[s], -1, d) != -1) { s_bad = 1; continue; }      // sends the segment twice
+            ord[s] = static_cast<int32_t>(e);
+            atomicAdd(&nchild[d], 1);
+            atomicAdd(&s_count, 1);
+        }
     }
     __syncthreads();
     if (s_count != p - 1) s_bad = 1;
@@ -137,10 +163,14 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
         if (i == 0 || parent[i] < 0) { ci[i] = 0; continue; }
         const int32_t par = parent[i], oi = ord[i];
         int32_t c = 0;
-        for (int s = 1; s < p; ++s) {
-            if (parent[s] == par && ord[s] < oi) ++c;
-            if (parent[s] == i && ord[s] > oi) s_bad = 1;
+        bool late_child = false;
+#pragma unroll 8
+        for (int s = 1; s < p; ++s) {                                         // reads of one address by all lanes, eight in flight
+            const int32_t ps = parent[s], os = ord[s];
+            c += (ps == par && os < oi) ? 1 : 0;
+            late_child = late_child || (ps == i && os > oi);
         }
+        if (late_child) s_bad = 1;
         ci[i] = c;
         if (c == 0) fchild[par] = i;
     }
@@ -158,8 +188,11 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
         if (i != 0 && ci[i] > 0) {
             off = 1;
             const int32_t par = parent[i], me = ci[i];
-            for (int s = 1; s < p; ++s)
-                if (parent[s] == par && ci[s] < me) off += size[s];
+#pragma unroll 8
+            for (int s = 1; s < p; ++s) {
+                const int32_t ps = parent[s], cs = ci[s], zs = size[s];
+                off += (ps == par && cs < me) ? zs : 0;
+            }
         }
         offStart[i] = off;
     }
@@ -192,8 +225,13 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
         prog[static_cast<size_t>(k) * p + pos] = static_cast<uint32_t>(i) | (static_cast<uint32_t>(push) << 20) |
                                                  (static_cast<uint32_t>(npop) << 21);
     }
-    if (deepest + 1 > kStackDepth) flags[1] = 1;
-    atomicMax(&flags[2], deepest + 1);
+    // one update of the global flags per block: thousands of atomic operations on one address would queue up
+    atomicMax(&s_deep, deepest + 1);
+    __syncthreads();
+    if (tid == 0) {
+        if (s_deep > kStackDepth) flags[1] = 1;
+        atomicMax(&flags[2], s_deep);
+    }
 }
 
 // The combine operation of a replay.  Sum: wrapping for integers, one IEEE addition (no FMA) for floating point.
