@@ -158,21 +158,31 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
     __syncthreads();
     if (s_count != p - 1) s_bad = 1;
     __syncthreads();
-    // 2. position among the senders to the same receiver; a processor sends after all it receives
-    for (int i = tid; i < p; i += kBuildThreads) {
-        if (i == 0 || parent[i] < 0) { ci[i] = 0; continue; }
-        const int32_t par = parent[i], oi = ord[i];
+    // 2. position among the senders to the same receiver; a processor sends after all it receives.  Every processor
+    //    looks at every other one: a wavefront loads 64 entries at a time, one per lane, and hands them round
+    //    lane by lane (a lane's register is read by all others), so the inner loop touches no memory.
+    const int lane = tid & (kWave - 1);
+    for (int i0 = 0; i0 < p; i0 += kBuildThreads) {
+        const int i = i0 + tid;
+        const bool sender = i > 0 && i < p && parent[i] >= 0;
+        const int32_t par = sender ? parent[i] : -3, oi = sender ? ord[i] : 0;
         int32_t c = 0;
         bool late_child = false;
-#pragma unroll 8
-        for (int s = 1; s < p; ++s) {                                         // reads of one address by all lanes, eight in flight
-            const int32_t ps = parent[s], os = ord[s];
-            c += (ps == par && os < oi) ? 1 : 0;
-            late_child = late_child || (ps == i && os > oi);
+        for (int s0 = 0; s0 < p; s0 += kWave) {
+            const int sl = s0 + lane;
+            const int32_t pv = sl < p ? parent[sl] : -2, ov = sl < p ? ord[sl] : 0;
+#pragma unroll
+            for (int u = 0; u < kWave; ++u) {
+                const int32_t ps = __builtin_amdgcn_readlane(pv, u), os = __builtin_amdgcn_readlane(ov, u);
+                c += (ps == par && os < oi) ? 1 : 0;
+                late_child = late_child || (ps == i && os > oi);
+            }
         }
-        if (late_child) s_bad = 1;
-        ci[i] = c;
-        if (c == 0) fchild[par] = i;
+        if (i < p) {
+            if (sender && late_child) s_bad = 1;
+            ci[i] = sender ? c : 0;
+            if (sender && c == 0) fchild[par] = i;
+        }
     }
     __syncthreads();
     if (s_bad) { if (tid == 0) flags[0] = 1; return; }
@@ -183,18 +193,23 @@ __global__ __launch_bounds__(kBuildThreads) void replay_build(int32_t p, int32_t
     __syncthreads();
     // 4. where a child's part starts relative to its parent's part: the first child starts with
     //    the parent; later ones after the first child's part, the parent itself and the earlier siblings
-    for (int i = tid; i < p; i += kBuildThreads) {
+    for (int i0 = 0; i0 < p; i0 += kBuildThreads) {
+        const int i = i0 + tid;
+        const bool later = i > 0 && i < p && ci[i] > 0;
+        const int32_t par = later ? parent[i] : -3, me = later ? ci[i] : 0;
         int32_t off = 0;
-        if (i != 0 && ci[i] > 0) {
-            off = 1;
-            const int32_t par = parent[i], me = ci[i];
-#pragma unroll 8
-            for (int s = 1; s < p; ++s) {
-                const int32_t ps = parent[s], cs = ci[s], zs = size[s];
+        for (int s0 = 0; s0 < p; s0 += kWave) {
+            const int sl = s0 + lane;
+            const bool has = sl >= 1 && sl < p;
+            const int32_t pv = has ? parent[sl] : -2, cv = has ? ci[sl] : 0, zv = has ? size[sl] : 0;
+#pragma unroll
+            for (int u = 0; u < kWave; ++u) {
+                const int32_t ps = __builtin_amdgcn_readlane(pv, u), cs = __builtin_amdgcn_readlane(cv, u),
+                              zs = __builtin_amdgcn_readlane(zv, u);
                 off += (ps == par && cs < me) ? zs : 0;
             }
         }
-        offStart[i] = off;
+        if (i < p) offStart[i] = later ? off + 1 : 0;
     }
     __syncthreads();
     for (int i = tid; i < p; i += kBuildThreads) {
