@@ -376,9 +376,14 @@ __global__ __launch_bounds__(kReplayThreads) void replay_kernel(int32_t p, const
     if (flags[0] | flags[1]) return;
     const int need = flags[2];
     if (need > D || need <= D - 8) return;                     // another depth variant takes this schedule
-    const int k = blockIdx.y;
+    // Workgroups go to the eight XCDs in turn (workgroup b to XCD b mod 8): the tiles are renumbered so that each
+    // XCD streams one contiguous eighth of the (segment, chunk) tiles instead of every eighth 2 KB chunk.
+    const unsigned tiles = gridDim.x * gridDim.y, b = blockIdx.y * gridDim.x + blockIdx.x;
+    const unsigned xcd = b & 7u, each = tiles >> 3, extra = tiles & 7u;
+    const unsigned tile = xcd * each + (xcd < extra ? xcd : extra) + (b >> 3);
+    const int k = static_cast<int>(tile / gridDim.x);
     const int64_t lo = offsets[k], hi = offsets[k + 1];
-    const int64_t b0 = lo + static_cast<int64_t>(blockIdx.x) * kReplayThreads * VEC;
+    const int64_t b0 = lo + static_cast<int64_t>(tile % gridDim.x) * kReplayThreads * VEC;
     if (b0 >= hi) return;
     const int64_t e0 = b0 + static_cast<int64_t>(threadIdx.x) * VEC;
     const uint32_t *pg = prog + static_cast<size_t>(k) * p;
